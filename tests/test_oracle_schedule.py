@@ -1,0 +1,318 @@
+"""Pins of the integer oracle (schedule re-application, index map, sweep selection, Eq. 1).
+
+Fixtures under tests/golden/ hold what the paper prints (Section 4.1's Split
+example, Algorithm 1's split chains, Table 2 / Table 3, Section 5.2's pair
+counts); the rest are invariants checked by brute force.
+"""
+import itertools
+import os
+
+import pytest
+
+from oracle import schedule as S
+from paper_2201_05587_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def lines(name):
+    with open(os.path.join(GOLD, name)) as f:
+        for ln in f:
+            ln = ln.strip()
+            if ln and not ln.startswith("#"):
+                yield ln
+
+
+def oshape(k: wl.Kernel):
+    s = k.shape
+    if k.is_conv():
+        return S.conv_shape(s.n, s.c, s.h, s.w, s.k, s.r, s.s, s.stride_h, s.stride_w, s.pad_h, s.pad_w, s.dtype)
+    return S.gemm_shape(s.batch, s.m, s.n, s.k, s.trans_b, s.dtype)
+
+
+# ---- Split (Section 4.1 / 4.2) -------------------------------------------------------------------
+def test_split_examples_from_the_paper():
+    for ln in lines("split_examples.txt"):
+        kind, extent, a, b, exp = ln.split()
+        if kind == "fixed":
+            assert S.split_fixed(int(extent), int(a), int(b)) == bool(int(exp))
+        else:
+            res = S.split(int(extent), int(a), strict=True)
+            assert (-1 if res is None else res[0]) == int(exp)
+            if res is not None:
+                assert res[1] == int(a) and res[0] * res[1] == int(extent)
+
+
+def test_split_guarded_tail_reading():
+    assert S.split(12, 8, strict=False) == (2, 8)      # ceil(12 / 8) outer iterations, tail guarded
+    assert S.split(4, 8, strict=False) is None          # factor larger than the loop: always invalid
+    assert S.split(49, 32, strict=False) == (2, 32)     # 7x7 map: 32 fits with a 17-row tail, 64 does not
+    assert S.split(49, 64, strict=False) is None
+
+
+def test_algorithm1_split_chains_transfer_both_ways():
+    fused = {}
+    outer = {}
+    for ln in lines("alg1_split_chains.txt"):
+        if ln.startswith("fused"):
+            _, name, f512, f1024 = ln.split()
+            fused[name] = (int(f512), int(f1024))
+            continue
+        head, e512, e1024 = [p.strip() for p in ln.split("|")]
+        name, axis, start, factors = head.split()
+        factors = [int(v) for v in factors.split(",")]
+        for size, exp in ((512, e512), (1024, e1024)):
+            extent = size if start == "full" else int(start)
+            got = S.replay_split_chain(extent, factors, strict=True)
+            assert got is not None, (name, axis, size)          # every transformation stays valid
+            assert list(got) == [int(v) for v in exp.split(",")], (name, axis, size)
+            prod = 1
+            for v in got:
+                prod *= v
+            assert prod == extent
+            outer[(name, axis, size)] = got[0]
+    for name, (f512, f1024) in fused.items():
+        assert outer[(name, "N", 512)] * outer[(name, "M", 512)] == f512
+        assert outer[(name, "N", 1024)] * outer[(name, "M", 1024)] == f1024
+
+
+# ---- apply ---------------------------------------------------------------------------------------
+E = S.CLS_CONV2D_BIAS_RELU
+
+
+def cfg1_shape():
+    return S.conv_shape(1, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, S.DT_F32)
+
+
+def test_apply_derives_outer_extents_from_the_target():
+    rec = S.record(E, S.SK_MFMA, 64, 32, 32, 32, 32, 32, 2, 1, 4, 2, 2)
+    donor = S.apply(rec, E, S.conv_shape(1, 128, 28, 28, 128, 3, 3, 1, 1, 1, 1))
+    target = S.apply(rec, E, cfg1_shape())
+    assert donor["status"] == S.OK and target["status"] == S.OK
+    # inner factors unchanged, outer extents follow the shape
+    for f in ("tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfma"):
+        assert donor[f] == target[f] == rec[f]
+    assert (donor["M"], donor["N"], donor["K"]) == (784, 128, 1152)
+    assert (target["M"], target["N"], target["K"]) == (3136, 64, 576)
+    assert (donor["tiles_m"], donor["tiles_n"], donor["k_tiles"]) == (13, 4, 36)
+    assert (target["tiles_m"], target["tiles_n"], target["k_tiles"]) == (49, 2, 18)
+    assert donor["tail_m"] == 784 - 12 * 64 and target["tail_m"] == 64
+    assert target["eff_split_k"] == 2 and target["k_iters"] == 9
+    assert target["grid"] == 49 * 2 * 2 and target["block"] == 64 * 2
+    assert target["workspace_bytes"] == 4 * 2 * 3136 * 64
+    assert target["lds_bytes"] == 2 * (64 + 32) * (32 + 4) * 4
+
+
+def test_factor_larger_than_loop_is_invalid_and_wrong_class_is_mismatch():
+    s7 = S.conv_shape(1, 512, 7, 7, 512, 3, 3, 1, 1, 1, 1)  # M = 49
+    assert S.apply(S.record(E, tile_m=64), E, s7)["status"] == S.ERR_INVALID_SCHEDULE
+    assert S.apply(S.record(E, tile_m=64), E, s7)["reason"] == S.R_FACTOR_GT_M
+    ok = S.apply(S.record(E, tile_m=32, wave_m=32), E, s7)
+    assert ok["status"] == S.OK and ok["tiles_m"] == 2 and ok["tail_m"] == 17
+    strict = S.apply(S.record(E, tile_m=32, wave_m=32), E, s7, S.STRICT_DIVISIBLE)
+    assert strict["status"] == S.ERR_INVALID_SCHEDULE and strict["reason"] == S.R_NOT_DIVISIBLE
+    pw = S.conv_shape(1, 16, 112, 112, 96, 1, 1)  # K = 16
+    assert S.apply(S.record(S.CLS_CONV2D_BIAS_RELU6, tile_k=32), S.CLS_CONV2D_BIAS_RELU6, pw)["reason"] == S.R_FACTOR_GT_K
+    assert S.apply(S.record(E, tile_n=128, wave_n=32), E, cfg1_shape())["reason"] == S.R_FACTOR_GT_N
+    # Section 4.2: a class-E schedule on a dense (class D) kernel is always invalid
+    d = S.gemm_shape(1, 64, 1000, 512, 1)
+    assert S.apply(S.record(E), S.CLS_DENSE_ADD, d)["status"] == S.ERR_CLASS_MISMATCH
+    assert S.apply(S.record(S.CLS_CONV2D_BIAS_ADD_RELU), E, cfg1_shape())["status"] == S.ERR_CLASS_MISMATCH
+
+
+def test_split_k_and_resource_validity():
+    sh = S.conv_shape(1, 64, 56, 56, 128, 1, 1, 2, 2)  # K = 64
+    r = S.record(S.CLS_CONV2D_ADD, tile_k=32, split_k=4)
+    p = S.apply(r, S.CLS_CONV2D_ADD, sh)
+    assert p["status"] == S.ERR_INVALID_SCHEDULE and p["reason"] == S.R_SPLIT_K  # only 2 K tiles
+    p = S.apply(S.record(E, tile_k=32, split_k=4), E, cfg1_shape())   # 18 K tiles
+    assert (p["k_iters"], p["eff_split_k"]) == (5, 4)
+    p = S.apply(S.record(E, tile_k=32, split_k=7), E, cfg1_shape())   # ceil(18/7)=3 -> 6 non-empty splits
+    assert (p["k_iters"], p["eff_split_k"]) == (3, 6)
+    big = S.record(E, S.SK_MFMA, 256, 256, 128, 64, 64, 32, 1, 0, 4, 1, 2)
+    p = S.apply(big, E, S.conv_shape(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1))
+    assert p["status"] == S.ERR_INVALID_SCHEDULE and p["reason"] == S.R_LDS
+    # bf16 with the 16-wide matrix block consumes 32 K per fetch: tile_k = 16 cannot hold one
+    bsh = S.gemm_shape(1, 256, 256, 256, 1, S.DT_BF16)
+    p = S.apply(S.record(S.CLS_DENSE_ADD, tile_k=16, mfma=16), S.CLS_DENSE_ADD, bsh)
+    assert p["reason"] == S.R_K_GRANULE
+    assert S.apply(S.record(S.CLS_DENSE_ADD, tile_k=16, mfma=32), S.CLS_DENSE_ADD, bsh)["status"] == S.OK
+
+
+def test_vector_width_and_unroll_are_reformulated_not_rejected():
+    stem = S.conv_shape(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)  # K = 147 (odd), stride 2
+    p = S.apply(S.record(E, vec=4, unroll=512), E, stem)
+    assert p["status"] == S.OK and (p["eff_vec_a"], p["eff_vec_b"], p["eff_vec_c"]) == (1, 1, 4)
+    assert p["eff_unroll"] == 1  # tile_k 16 with the 16-wide fp32 block is a single step
+    p = S.apply(S.record(E, vec=4, tile_k=32, mfma=32, unroll=512), E, cfg1_shape())
+    assert (p["eff_vec_a"], p["eff_vec_b"], p["eff_vec_c"], p["eff_unroll"]) == (4, 4, 4, 4)
+    s14 = S.conv_shape(1, 256, 14, 14, 256, 3, 3, 1, 1, 1, 1)
+    assert S.apply(S.record(E, vec=4), E, s14)["eff_vec_a"] == 2    # rows of 14 outputs
+    pw = S.conv_shape(1, 96, 14, 14, 576, 1, 1, dtype=S.DT_BF16)
+    assert S.apply(S.record(E, vec=8, tile_k=32), E, pw)["eff_vec_a"] == 4   # 196 = 4 * 49
+
+
+def test_malformed_records_and_shapes_are_argument_errors():
+    assert S.apply(S.record(E, wave_m=48), E, cfg1_shape())["status"] == S.ERR_BAD_ARG
+    assert S.apply(S.record(E, mfma=8), E, cfg1_shape())["status"] == S.ERR_BAD_ARG
+    assert S.apply(S.record(E, tile_m=256, tile_n=256, wave_m=16, wave_n=16), E, cfg1_shape())["status"] == S.ERR_BAD_ARG
+    assert S.apply(S.record(E, vec=3), E, cfg1_shape())["status"] == S.ERR_BAD_ARG
+    assert S.apply(S.record(E), E, S.conv_shape(1, 0, 8, 8, 4, 3, 3))["status"] == S.ERR_BAD_ARG
+    assert S.apply(S.record(E), E, S.conv_shape(1, 4, 2, 2, 4, 5, 5))["status"] == S.ERR_BAD_ARG
+    assert S.apply(S.record(E), 99, cfg1_shape())["status"] == S.ERR_BAD_ARG
+
+
+def all_cfg_kernels():
+    ks = [wl.cfg1_target(), wl.cfg1_donor()] + wl.resnet18_kernels() + wl.resnet50_kernels()
+    ks += wl.bert_kernels() + wl.bert_kernels(seq=256) + wl.mobilenetv2_kernels(1) + wl.mobilenetv2_kernels(16)
+    ks += wl.resnet50_kernels(32, wl.BF16, with_dense=False)
+    for i in range(3):
+        ks += wl.synthetic_network(i)
+    return ks
+
+
+def test_default_schedule_is_valid_for_every_configured_shape():
+    for k in all_cfg_kernels():
+        rec = S.default_schedule(k.cls, oshape(k))
+        p = S.apply(rec, k.cls, oshape(k))
+        assert p["status"] == S.OK, (k.name, rec, p)
+        assert S.apply(rec, k.cls, oshape(k), S.STRICT_DIVISIBLE)["status"] in (S.OK, S.ERR_INVALID_SCHEDULE)
+    # and for degenerate tiny shapes, through the one-thread-per-output record
+    tiny = S.conv_shape(1, 2, 4, 4, 3, 3, 3, 1, 1, 1, 1)
+    assert S.default_schedule(E, tiny)["sketch"] == S.SK_DIRECT
+    assert S.apply(S.default_schedule(E, tiny), E, tiny)["status"] == S.OK
+    assert S.apply(S.default_schedule(S.CLS_DENSE_ADD, S.gemm_shape(1, 1, 3, 5, 1)), S.CLS_DENSE_ADD,
+                   S.gemm_shape(1, 1, 3, 5, 1))["status"] == S.OK
+
+
+# ---- index map -----------------------------------------------------------------------------------
+def check_cover(plan):
+    """Every (batch, m, n, k) cell is owned by exactly one workgroup; the map is a bijection."""
+    seen_tiles = set()
+    area = 0
+    for wg in range(plan["grid"]):
+        b, z, m0, me, n0, ne, k0, ke = S.plan_tile(plan, wg)
+        assert me >= 1 and ne >= 1 and ke >= 1
+        assert m0 + me <= plan["M"] and n0 + ne <= plan["N"] and k0 + ke <= plan["K"]
+        assert m0 % plan["tile_m"] == 0 and n0 % plan["tile_n"] == 0
+        key = (b, z, m0, n0, k0)
+        assert key not in seen_tiles
+        seen_tiles.add(key)
+        area += me * ne * ke
+    slabs_hi = plan["batch"] if plan["sketch"] != S.SK_DWCONV else 1
+    assert area == slabs_hi * plan["M"] * plan["N"] * plan["K"]
+
+
+@pytest.mark.parametrize("order", range(6))
+def test_index_map_is_a_bijection_that_tiles_the_iteration_space(order):
+    shapes = [
+        (E, S.conv_shape(1, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1)),
+        (E, S.conv_shape(1, 512, 7, 7, 512, 3, 3, 1, 1, 1, 1)),
+        (E, S.conv_shape(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)),
+        (S.CLS_BATCH_MATMUL, S.gemm_shape(5, 128, 64, 128, 0, S.DT_BF16)),
+        (S.CLS_DENSE_ADD, S.gemm_shape(1, 1024, 1000, 768, 1, S.DT_BF16)),
+    ]
+    for (cls, sh), (tm, tn, sk) in itertools.product(shapes, [(32, 32, 1), (32, 64, 3), (16, 16, 2)]):
+        rec = S.record(cls, S.SK_MFMA, tm, tn, 32, 16, 16, 16, sk, order, 4, 1, 2)
+        p = S.apply(rec, cls, sh)
+        if p["status"] != S.OK:
+            continue
+        check_cover(p)
+    dw = S.conv_shape(2, 48, 14, 14, 48, 3, 3, 2, 2, 1, 1)
+    p = S.apply(S.record(S.CLS_DWCONV_BIAS_RELU6, S.SK_DWCONV, 4, 4, 8, 1, 1, 0, 1, order, 1, 1, 1),
+                S.CLS_DWCONV_BIAS_RELU6, dw)
+    assert p["status"] == S.OK
+    check_cover(p)
+
+
+def test_index_map_orders_by_hand():
+    sh = S.gemm_shape(1, 96, 64, 64, 1)   # 3 x 2 tiles of 32
+    def tiles(order):
+        p = S.apply(S.record(S.CLS_DENSE_ADD, S.SK_MFMA, 32, 32, 16, 32, 32, 16, 1, order), S.CLS_DENSE_ADD, sh)
+        return [(t[2] // 32, t[4] // 32) for t in (S.plan_tile(p, w) for w in range(p["grid"]))]
+    assert tiles(0) == [(0, 0), (1, 0), (2, 0), (0, 1), (1, 1), (2, 1)]
+    assert tiles(1) == [(0, 0), (0, 1), (1, 0), (1, 1), (2, 0), (2, 1)]
+    assert tiles(2) == tiles(0)  # fewer than GROUP_M tiles: one band
+    # 6 workgroups over 8 XCDs: XCD x holds logical id x
+    assert tiles(3) == tiles(0)
+    sh = S.gemm_shape(1, 32 * 20, 32, 64, 1)  # 20 x 1 tiles -> XCD x gets ids {x, x+8, x+16}
+    p = S.apply(S.record(S.CLS_DENSE_ADD, S.SK_MFMA, 32, 32, 16, 32, 32, 16, 1, 3), S.CLS_DENSE_ADD, sh)
+    got = [S.plan_tile(p, w)[2] // 32 for w in range(20)]
+    # XCDs 0..3 own 3 tiles, 4..7 own 2: XCD0 -> 0,1,2; XCD1 -> 3,4,5; ...; XCD4 -> 12,13; ...
+    assert got[0] == 0 and got[8] == 1 and got[16] == 2 and got[1] == 3 and got[4] == 12 and got[12] == 13
+    assert sorted(got) == list(range(20))
+
+
+def test_grouped_order_walks_bands_of_eight():
+    sh = S.gemm_shape(1, 32 * 10, 32 * 3, 64, 1)
+    p = S.apply(S.record(S.CLS_DENSE_ADD, S.SK_MFMA, 32, 32, 16, 32, 32, 16, 1, 2), S.CLS_DENSE_ADD, sh)
+    got = [(t[2] // 32, t[4] // 32) for t in (S.plan_tile(p, w) for w in range(p["grid"]))]
+    assert got[:9] == [(0, 0), (1, 0), (2, 0), (3, 0), (4, 0), (5, 0), (6, 0), (7, 0), (0, 1)]
+    assert got[24:] == [(8, 0), (9, 0), (8, 1), (9, 1), (8, 2), (9, 2)]
+
+
+# ---- sweep selection (Section 4.3) ---------------------------------------------------------------
+def test_selection_on_a_hand_made_time_matrix():
+    kc = [1, 1, 2, 4]
+    pc = [1, 1, 0, 4, 1]
+    pair = [
+        [5.0, 3.0, 9.0, 9.0, -1.0],   # donor 1 wins; donor 4 invalid; donors 2, 3 are other classes
+        [7.0, 7.5, 0.1, 0.1, 8.0],    # default (6.0) wins; cheap times of other classes are ignored
+        [1.0, 1.0, 1.0, 1.0, 1.0],    # class 2 has no donor -> default
+        [9.0, 9.0, 9.0, 2.0, 9.0],    # tie with the default -> default
+    ]
+    default = [4.0, 6.0, 3.0, 2.0]
+    rows = S.select(kc, pc, pair, default)
+    assert rows == [(1, 3.0, 2, 1), (-1, 6.0, 3, 0), (-1, 3.0, 0, 0), (-1, 2.0, 1, 0)]
+    pair[0][0] = 3.0  # equal donors: lowest index
+    assert S.select(kc, pc, pair, default)[0][0] == 0
+    assert S.select(kc, pc, pair, default, allow_slower_than_default=True)[1] == (0, 7.0, 3, 0)
+
+
+def parse_table2():
+    models, pairs, kernels, r18 = {}, [], {}, {}
+    for ln in lines("table2_model_classes.txt"):
+        tok = ln.split()
+        if tok[0] == "pairs":
+            pairs.append((tok[1], tok[2], int(tok[3]), int(tok[4])))
+        elif tok[0] == "kernels":
+            kernels[tok[1]] = int(tok[2])
+        elif tok[0] == "resnet18":
+            r18 = {t.split(":")[0]: int(t.split(":")[1]) for t in tok[1:]}
+        else:
+            left, tuning, top3 = [p.strip() for p in ln.split("|")]
+            lt = left.split()
+            cls = {t.split(":")[0]: (int(t.split(":")[1]), int(t.split(":")[2])) for t in lt[2:]}
+            models[lt[0]] = dict(name=lt[1], cls=cls, tuning=tuning, top3=top3.split())
+    return models, pairs, kernels, r18
+
+
+def test_evaluation_counts_match_the_papers_pair_counts():
+    models, pairs, kernels, r18 = parse_table2()
+
+    def kernel_list(m):
+        return [c for c, (n, _) in models[m]["cls"].items() for _ in range(n)]
+    for target, donor, n_pairs, n_kernels in pairs:
+        assert len(kernel_list(target)) == n_kernels
+        assert S.evaluation_count(kernel_list(target), kernel_list(donor)) == n_pairs
+    assert len(kernel_list("M7")) == kernels["M7"]
+    # ResNet18 with ResNet50's schedules (Section 4.3): A has 4 donors, E 16, B/C/D one each, F none
+    r18_list = [c for c, n in r18.items() for _ in range(n)]
+    assert len(r18_list) == 18
+    assert S.evaluation_count(r18_list, kernel_list("M1")) == 3 * 5 + 8 * 17 + 4 * 1 + 3 * 2
+
+
+def test_equation1_reproduces_table2_and_table3():
+    models, _, _, _ = parse_table2()
+    for mid, m in models.items():
+        cost = {c: pct / 100.0 for c, (_, pct) in m["cls"].items()}
+        scores = {}
+        for tid, t in models.items():
+            if tid == mid:
+                continue
+            scores[tid] = S.model_selection_score(cost, {c: n for c, (n, _) in t["cls"].items()})
+        ranked = sorted(scores, key=lambda t: -scores[t])
+        assert ranked[0] == m["tuning"], (mid, ranked[:3])
+        for pos, want in enumerate(m["top3"]):
+            if want != "-":
+                assert ranked[pos] == want, (mid, pos, ranked[:3])
