@@ -1,0 +1,310 @@
+/*
+ * libtt - fused DNN operator kernels executed under transferable schedule
+ * records, and the transfer-tuning sweep, for AMD Instinct MI355X (gfx950).
+ *
+ * The vocabulary follows "Transfer-Tuning: Reusing Auto-Schedules for
+ * Efficient Tensor Program Code Generation" (Gibson & Cano, PACT 2022):
+ *
+ *   kernel        a fused operator group handed to the tuner as one loop nest
+ *                 (Section 4.2), e.g. conv2d + bias + ReLU (Algorithm 2);
+ *   kernel class  all kernels with the same operator sequence, any sizes
+ *                 (Section 4.2); schedules are reused only inside a class;
+ *   schedule      the list of loop transformations a kernel is compiled with
+ *                 (Section 4.1: Split, Reorder, Fuse, Parallel, Unroll,
+ *                 Vectorize, ComputeAt, cache buffer).  Here: one fixed-size
+ *                 record of the GPU-native knobs those primitives map to;
+ *   transfer      re-applying a schedule tuned for one kernel to another kernel
+ *                 of the class: inner factors are kept, outer extents are
+ *                 derived from the new shape, and a record that cannot fit is
+ *                 invalid (Sections 4.1, 4.2);
+ *   sweep         trying every same-class donor schedule on every target
+ *                 kernel, standalone, and keeping the fastest, with the default
+ *                 schedule as fallback (Section 4.3).
+ *
+ * Conventions of every entry point
+ *   - plain C ABI; every function returns a tt_status (0 = TT_OK, negative = error);
+ *   - pointers named x, w, bias, residual, y, a, b, c, ws and `out_dev` are DEVICE
+ *     pointers, 16-byte aligned, owned by the caller; all other pointers are HOST
+ *     pointers.  The library never allocates or frees device memory;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
+ *     operator entry points only enqueue work on it and return; the caller
+ *     synchronises.  tt_transfer_sweep synchronises the stream itself;
+ *   - tensors are dense, row-major in the order written (NCHW activations, KCRS
+ *     filters); element type is tt_dtype of the shape; bias is always the same
+ *     type as the activations; accumulation is always float32;
+ *   - an operator entry point given a schedule that is invalid for the shape
+ *     returns the error and writes nothing: falling back to the default schedule
+ *     is the sweep's decision (Section 4.3), not the operator's.  A NULL schedule
+ *     means "the default schedule of this kernel";
+ *   - split-K partial sums live in the caller's workspace `ws`; its size for a
+ *     given (schedule, shape) is tt_plan.workspace_bytes.  Too small a workspace
+ *     is TT_ERR_WORKSPACE.
+ */
+#ifndef TT_H
+#define TT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Kernel classes (Section 4.2).  Letters are the paper's labels for ResNet18 (Table 1). */
+typedef enum tt_class {
+    TT_CONV2D_ADD = 0,           /* A: conv2d + per-output-channel vector, no activation        */
+    TT_CONV2D_BIAS_RELU = 1,     /* E: pad, conv2d, + bias, ReLU (Algorithm 2)                  */
+    TT_CONV2D_BIAS_ADD_RELU = 2, /* F: conv2d, + bias, + residual tensor, ReLU                  */
+    TT_CONV2D_BIAS_RELU6 = 3,    /* conv2d, + bias, clamp to [0,6] (MobileNetV2-shaped nets)    */
+    TT_DENSE_ADD = 4,            /* D: dense + vector                                           */
+    TT_DENSE_BIAS_RELU = 5,
+    TT_DENSE_BIAS_GELU = 6,      /* exact GELU: x/2 * (1 + erf(x / sqrt 2))                      */
+    TT_BATCH_MATMUL = 7,
+    TT_DWCONV_BIAS_RELU6 = 8,    /* depthwise 3x3 conv, + bias, clamp to [0,6]                  */
+    TT_NUM_CLASSES = 9
+} tt_class;
+
+typedef enum tt_dtype { TT_F32 = 0, TT_BF16 = 1 } tt_dtype;
+
+typedef enum tt_status {
+    TT_OK = 0,
+    TT_ERR_INVALID_SCHEDULE = -1, /* the record cannot be applied to this shape (Section 4.2: a split
+                                     factor larger than the loop; Section 4.3 reports such pairs as -1) */
+    TT_ERR_CLASS_MISMATCH = -2,   /* record of another kernel class (Section 4.2: always invalid)      */
+    TT_ERR_BAD_ARG = -3,          /* NULL / misaligned pointer, ill-formed shape or record             */
+    TT_ERR_WORKSPACE = -4,        /* workspace smaller than tt_plan.workspace_bytes                    */
+    TT_ERR_UNSUPPORTED = -5,      /* valid plan, but no compiled kernel variant implements it          */
+    TT_ERR_HIP = -6               /* a HIP runtime call failed                                         */
+} tt_status;
+
+/* Why a record is invalid for a shape (tt_plan.reason when status == TT_ERR_INVALID_SCHEDULE). */
+typedef enum tt_reason {
+    TT_R_NONE = 0,
+    TT_R_FACTOR_GT_M = 1,  /* tile_m larger than the M loop (Section 4.2)                */
+    TT_R_FACTOR_GT_N = 2,
+    TT_R_FACTOR_GT_K = 3,
+    TT_R_NOT_DIVISIBLE = 4,/* only with TT_STRICT_DIVISIBLE (Section 4.1: {N : f | N})   */
+    TT_R_SPLIT_K = 5,      /* more reduction splits than K tiles                         */
+    TT_R_LDS = 6,          /* staged tiles exceed the 160 KiB of LDS a workgroup can use */
+    TT_R_K_GRANULE = 7,    /* tile_k is not a multiple of what one matrix-core step of
+                              this data type consumes                                    */
+    TT_R_GRID = 8,         /* more than 2^31 - 1 workgroups                              */
+    TT_R_SKETCH_CLASS = 9  /* the record's sketch has no meaning for this class          */
+} tt_reason;
+
+/* The loop-nest skeleton ("sketch") a record's factors refer to. */
+typedef enum tt_sketch {
+    TT_SK_MFMA = 0,   /* contraction: workgroup tile -> wave tile -> matrix-core block; LDS-staged K loop */
+    TT_SK_GEMV = 1,   /* dense classes: a wave per few outputs, lanes split K, wave reduction            */
+    TT_SK_DWCONV = 2, /* depthwise: (planes, rows, cols) tile per workgroup, micro-tile per thread       */
+    TT_SK_DIRECT = 3  /* any class: one thread per output, the unscheduled loop nest                     */
+} tt_sketch;
+
+/* NCHW activations [n,c,h,w]; KCRS filters [k,c,r,s] ([c,1,r,s] for depthwise, with k == c).
+ * Cross-correlation, zero padding, dilation 1, groups 1 (Algorithm 2). */
+typedef struct tt_conv_shape {
+    int32_t n, c, h, w, k, r, s, stride_h, stride_w, pad_h, pad_w;
+    int32_t dtype; /* tt_dtype */
+} tt_conv_shape;
+
+/* C[b,m,n] = sum_k A[b,m,k] * B(b,k,n).  A is [batch,m,k]; B is [batch,n,k] when trans_b = 1
+ * and [batch,k,n] when trans_b = 0.  Dense kernels: batch = 1, trans_b = 1, B = weights [out,in]. */
+typedef struct tt_gemm_shape {
+    int32_t batch, m, n, k, trans_b;
+    int32_t dtype; /* tt_dtype */
+} tt_gemm_shape;
+
+/*
+ * A schedule record.  Every field is an INNER factor or a mode; nothing in it
+ * depends on the size of the kernel it was tuned for, so it can be re-applied
+ * to any kernel of its class (Section 4.1's Split(N, N/8, 8) form).
+ *
+ * Meaning per sketch (GEMM view: conv M = n*Ho*Wo, N = k, K = c*r*s; dense and
+ * batch matmul M, N, K per batch; depthwise M = Ho, N = Wo, "K" = n*c planes):
+ *   TT_SK_MFMA   tile_m x tile_n x tile_k workgroup tile (Split level 1, powers of two 16..256,
+ *                tile_k in 16/32/64/128); wave_m x wave_n wave tile (Split level 2); mfma = edge
+ *                of the matrix-core block, 16 or 32 (innermost Split); split_k = parallel split of
+ *                the reduction (Parallel on a reduction axis); order = workgroup raster (Reorder +
+ *                Fuse of the two parallel axes, see tt_plan_tile); vec = elements per global access
+ *                (Vectorize); unroll = depth to which the per-tile K-step loop is unrolled (Unroll);
+ *                stages = LDS buffers, 1 or 2 (cache buffer + ComputeAt).
+ *   TT_SK_GEMV   tile_m (= wave_m) rows and tile_n outputs per workgroup, wave_n outputs per wave,
+ *                tile_k = K elements a wave consumes per step (64 lanes x 1/2/4/8), mfma = 0.
+ *   TT_SK_DWCONV tile_m x tile_n output rows x cols and tile_k planes per workgroup, wave_m x wave_n
+ *                outputs per thread, stages = 2 stages the input patch through LDS, mfma = 0.
+ *   TT_SK_DIRECT all tile and wave fields 1, mfma = 0.
+ */
+typedef struct tt_schedule {
+    int32_t cls;    /* tt_class the record was tuned for */
+    int32_t sketch; /* tt_sketch */
+    int32_t tile_m, tile_n, tile_k;
+    int32_t wave_m, wave_n;
+    int32_t mfma;
+    int32_t split_k;
+    int32_t order;  /* 0 M-tiles fastest, 1 N-tiles fastest, 2 bands of 8 M-tiles; +3 = XCD-contiguous */
+    int32_t vec;    /* 1, 2, 4 or 8 */
+    int32_t unroll; /* >= 1 */
+    int32_t stages; /* 1 or 2 */
+    /* provenance (ignored by tt_schedule_apply): */
+    int32_t id;              /* caller's identifier of the record                     */
+    int32_t donor_shape[12]; /* the shape the record was tuned on (struct as int32[]) */
+    float donor_us;          /* its time on that shape                                */
+} tt_schedule;
+
+/*
+ * The integer plan tt_schedule_apply derives.  All fields up to workspace_bytes
+ * are a pure function of (record, class, shape, flags) and are specified
+ * independently of the kernels; variant_id is the library's own lookup.
+ */
+typedef struct tt_plan {
+    int32_t status, reason;
+    int32_t sketch, batch, M, N, K;
+    int32_t tile_m, tile_n, tile_k, wave_m, wave_n, mfma;
+    int32_t tiles_m, tiles_n, k_tiles;   /* derived outer extents = ceil(extent / factor) */
+    int32_t tail_m, tail_n, tail_k;      /* size of the last tile on each axis            */
+    int32_t eff_split_k, k_iters;        /* non-empty reduction splits; K tiles per split */
+    int32_t slabs;                       /* batch * eff_split_k (depthwise: plane tiles)  */
+    int32_t eff_vec_a, eff_vec_b, eff_vec_c; /* vector widths after reformulation         */
+    int32_t eff_unroll;
+    int32_t stages, order;
+    int32_t grid, block;                 /* workgroups, threads per workgroup             */
+    int32_t lds_bytes;
+    int64_t workspace_bytes;
+    int32_t variant_id;                  /* compiled kernel variant, -1 if none           */
+    int32_t reserved;
+} tt_plan;
+
+enum { TT_STRICT_DIVISIBLE = 1 }; /* flags of tt_schedule_apply: factors must divide their loops (Section 4.1) */
+
+/* Library version and a human-readable name for a status code (static storage). */
+int tt_version(void);
+const char *tt_status_name(int status);
+/* Text of the last failed HIP call on this thread (what, HIP's message, HIP's code); "" if none. */
+const char *tt_last_error(void);
+
+/*
+ * The default ("untuned") schedule of a kernel (Section 4.3): valid for every
+ * well-formed shape of the class.  `shape` is a tt_conv_shape for the conv and
+ * depthwise classes and a tt_gemm_shape otherwise (host pointers).
+ */
+int tt_schedule_default(int cls, const void *shape, tt_schedule *out);
+
+/*
+ * Re-apply a schedule record to a target kernel (Sections 4.1, 4.2): keep the
+ * inner factors, derive the outer extents from `shape`, decide validity.
+ * Host-only integer work.  Returns plan->status: TT_OK, TT_ERR_INVALID_SCHEDULE
+ * (plan->reason says why), TT_ERR_CLASS_MISMATCH or TT_ERR_BAD_ARG.
+ */
+int tt_schedule_apply(const tt_schedule *sched, int cls, const void *shape, int flags, tt_plan *plan);
+
+/*
+ * Host mirror of the device index map: workgroup id -> out[8] =
+ * {batch, k-split, m0, m_extent, n0, n_extent, k0, k_extent} (depthwise:
+ * {plane tile, 0, row0, rows, col0, cols, plane0, planes}).  Not defined for
+ * TT_SK_DIRECT (TT_ERR_BAD_ARG).
+ */
+int tt_plan_tile(const tt_plan *plan, int64_t wg, int32_t out[8]);
+
+/*
+ * Run the device's own index decode for every workgroup of the plan and write
+ * 8 int32 per workgroup to out_dev (device, 8 * plan->grid int32).  Used to
+ * check that host and device agree bit for bit.
+ */
+int tt_debug_tile_map(const tt_plan *plan, int32_t *out_dev, void *stream);
+
+/*
+ * conv2d (+bias) (+residual) (+activation) as an implicit GEMM (Algorithm 2; Table 1
+ * classes A, E, F).  cls selects the epilogue: TT_CONV2D_ADD (bias, none),
+ * TT_CONV2D_BIAS_RELU, TT_CONV2D_BIAS_ADD_RELU (residual required, same layout
+ * and type as y), TT_CONV2D_BIAS_RELU6.  x [n,c,h,w], w [k,c,r,s], bias [k],
+ * y [n,k,Ho,Wo], Ho = (h + 2 pad_h - r) / stride_h + 1.
+ */
+int tt_conv2d_bias_relu(const void *x, const void *w, const void *bias, const void *residual, void *y,
+                        const tt_conv_shape *shape, int cls, const tt_schedule *sched, void *ws,
+                        size_t ws_bytes, void *stream);
+
+/*
+ * dense (+bias) (+activation): y[m,o] = act(bias[o] + sum_i x[m,i] w[o,i]) (Table 1 class D;
+ * Section 4.4.1's dense-only class).  cls: TT_DENSE_ADD, TT_DENSE_BIAS_RELU,
+ * TT_DENSE_BIAS_GELU.  shape: batch = 1, trans_b = 1, m rows, n outputs, k inputs.
+ */
+int tt_dense_bias_relu(const void *x, const void *w, const void *bias, void *y, const tt_gemm_shape *shape,
+                       int cls, const tt_schedule *sched, void *ws, size_t ws_bytes, void *stream);
+
+/* Batch matmul c[b] = a[b] B[b] (the loop nest of Algorithm 1 per batch); class TT_BATCH_MATMUL. */
+int tt_batch_matmul(const void *a, const void *b, void *c, const tt_gemm_shape *shape,
+                    const tt_schedule *sched, void *ws, size_t ws_bytes, void *stream);
+
+/* Depthwise 3x3 conv + bias + clamp[0,6]; w [c,1,3,3]; class TT_DWCONV_BIAS_RELU6; float32 only. */
+int tt_dwconv(const void *x, const void *w, const void *bias, void *y, const tt_conv_shape *shape,
+              const tt_schedule *sched, void *stream);
+
+/* One target kernel of a sweep.  bufs: conv {x, w, bias, residual|NULL, y}; dense {x, w, bias, y, NULL};
+ * batch matmul {a, b, c, NULL, NULL}; depthwise {x, w, bias, y, NULL}. */
+typedef struct tt_kernel_desc {
+    int32_t cls;
+    int32_t use_count;  /* how often the network runs this kernel (Table 1's "Use Count") */
+    const void *shape;  /* host: tt_conv_shape or tt_gemm_shape                           */
+    void *bufs[5];      /* device                                                         */
+    void *ws;           /* device workspace for split-K records, may be NULL              */
+    size_t ws_bytes;
+} tt_kernel_desc;
+
+typedef struct tt_sweep_opts {
+    int32_t warmup;               /* untimed launches per pair (default 3)                              */
+    int32_t samples;              /* timed samples per pair, the median is kept (default 10)            */
+    int32_t min_sample_us;        /* launches per sample are chosen so a sample lasts this long (200)   */
+    int32_t max_launches;         /* cap on launches per sample (default 64)                            */
+    int32_t flags;                /* TT_STRICT_DIVISIBLE                                                */
+    int32_t allow_slower_than_default; /* 1: keep the best donor even if the default is faster         */
+} tt_sweep_opts;
+
+typedef struct tt_sweep_row {
+    int32_t kernel;
+    int32_t chosen;      /* index into the pool, -1 = the default schedule */
+    int32_t n_valid, n_invalid, n_other_class;
+    int32_t reserved;
+    double best_us, default_us;
+} tt_sweep_row;
+
+/*
+ * The transfer-tuning sweep (Section 4.3).  For each of the nk target kernels:
+ * time the default schedule, then every pool record of the kernel's class;
+ * records that do not apply are recorded as -1 and skipped; the fastest wins,
+ * the default is the fallback and wins ties, equal donors go to the lowest
+ * index.  rows (host, nk).  pair_us (host, nk * np doubles, may be NULL):
+ * median microseconds per launch, -1 for an invalid pair, -2 for a record of
+ * another class.  evaluations (host, may be NULL): number of timed pairs,
+ * sum_k (1 + same-class records).  wall_seconds (host, may be NULL): wall-clock of
+ * the call, the paper's "search time".  Synchronises `stream`.
+ */
+int tt_transfer_sweep(const tt_kernel_desc *kernels, int nk, const tt_schedule *pool, int np,
+                      const tt_sweep_opts *opts, void *stream, tt_sweep_row *rows, double *pair_us,
+                      int64_t *evaluations, double *wall_seconds);
+
+/*
+ * Time ONE (kernel, schedule) pair standalone with the sweep's protocol (warm-up,
+ * median of samples of back-to-back launches, HIP events on `stream`).
+ * sched NULL = default.  median_us / min_us: host.  Returns the apply status
+ * (then nothing was launched) or a launch error.
+ */
+int tt_time_pair(const tt_kernel_desc *kernel, const tt_schedule *sched, const tt_sweep_opts *opts,
+                 void *stream, double *median_us, double *min_us);
+
+/*
+ * Enumerate the schedule space of a class for a data type: every compiled
+ * kernel variant crossed with the run-time knobs (split_k, order, stages, vec,
+ * unroll).  Writes up to `cap` records to out (host) and returns the total
+ * count (call with cap = 0 to size the buffer).  The exhaustive "native" sweep
+ * of a kernel is tt_transfer_sweep over this pool.
+ */
+int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out, int cap);
+
+/* Pure selection step of the sweep on given times (host only; the rule tt_transfer_sweep uses). */
+int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t *pool_cls, int np, const double *pair_us,
+                    const double *default_us, int allow_slower_than_default, tt_sweep_row *rows);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TT_H */

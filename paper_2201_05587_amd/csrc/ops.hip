@@ -1,0 +1,346 @@
+// C-ABI operator entry points, standalone pair timing and the transfer-tuning sweep.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "tt_internal.h"
+
+using namespace tt;
+
+namespace tt {
+static thread_local char g_last_error[256] = "";
+int note_hip_error(int code, const char *where)
+{
+    snprintf(g_last_error, sizeof g_last_error, "%s: %s (%d)", where, hipGetErrorString((hipError_t)code), code);
+    return TT_ERR_HIP;
+}
+} // namespace tt
+
+extern "C" const char *tt_last_error(void) { return tt::g_last_error; }
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int conv_out(int in, int f, int stride, int pad) { return (in + 2 * pad - f) / stride + 1; }
+
+// Resolve the record (NULL = default), re-apply it to the shape, check the workspace.
+int make_plan(const tt_schedule *sched, int cls, const void *shape, const void *ws, size_t ws_bytes, tt_plan *plan)
+{
+    tt_schedule def;
+    if (!sched) {
+        const int rc = tt_schedule_default(cls, shape, &def);
+        if (rc != TT_OK) return rc;
+        sched = &def;
+    }
+    const int rc = tt_schedule_apply(sched, cls, shape, 0, plan);
+    if (rc != TT_OK) return rc;
+    if (plan->workspace_bytes > 0 && (!ws || (int64_t)ws_bytes < plan->workspace_bytes || !aligned16(ws)))
+        return TT_ERR_WORKSPACE;
+    return TT_OK;
+}
+
+void fill_common(ContractArgs &g, const tt_plan &plan, const tt_schedule *sched, int cls, int dtype)
+{
+    g.map = tile_map_of(plan);
+    g.batch = plan.batch;
+    g.M = plan.M;
+    g.N = plan.N;
+    g.K = plan.K;
+    g.eff_vec_a = plan.eff_vec_a;
+    g.eff_vec_b = plan.eff_vec_b;
+    g.eff_vec_c = plan.eff_vec_c;
+    g.stages = plan.stages;
+    g.unroll = plan.eff_unroll;
+    g.act = act_of_class(cls);
+    g.dtype = dtype;
+    (void)sched;
+}
+
+int run_contraction(ContractArgs &g, const tt_plan &plan, int family, void *stream)
+{
+    switch (plan.sketch) {
+    case TT_SK_DIRECT:
+        return launch_direct(g, family, plan.grid, stream);
+    case TT_SK_GEMV:
+        return launch_gemv(g, plan, stream);
+    case TT_SK_MFMA: {
+        if (plan.variant_id < 0 || plan.variant_id >= kNumVariants) return TT_ERR_UNSUPPORTED;
+        const int rc = kVariants[plan.variant_id].launch(g, plan.grid, plan.lds_bytes, stream);
+        if (rc != TT_OK) return rc;
+        if (plan.eff_split_k > 1) return launch_splitk_reduce(g, family, stream);
+        return TT_OK;
+    }
+    default:
+        return TT_ERR_UNSUPPORTED;
+    }
+}
+
+} // namespace
+
+extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bias, const void *residual, void *y,
+                                   const tt_conv_shape *shape, int cls, const tt_schedule *sched, void *ws,
+                                   size_t ws_bytes, void *stream)
+{
+    if (!x || !w || !y || !shape || !is_conv_class(cls)) return TT_ERR_BAD_ARG;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(residual))
+        return TT_ERR_BAD_ARG;
+    if ((cls == TT_CONV2D_BIAS_ADD_RELU) != (residual != nullptr)) return TT_ERR_BAD_ARG;
+    tt_plan plan;
+    const int rc = make_plan(sched, cls, shape, ws, ws_bytes, &plan);
+    if (rc != TT_OK) return rc;
+    ContractArgs g;
+    std::memset(&g, 0, sizeof g);
+    fill_common(g, plan, sched, cls, shape->dtype);
+    g.a = x;
+    g.b = w;
+    g.bias = bias;
+    g.res = residual;
+    g.out = y;
+    g.ws = static_cast<float *>(ws);
+    g.has_bias = bias != nullptr;
+    g.has_res = residual != nullptr;
+    g.C = shape->c;
+    g.H = shape->h;
+    g.W = shape->w;
+    g.R = shape->r;
+    g.S = shape->s;
+    g.stride_h = shape->stride_h;
+    g.stride_w = shape->stride_w;
+    g.pad_h = shape->pad_h;
+    g.pad_w = shape->pad_w;
+    g.Ho = conv_out(shape->h, shape->r, shape->stride_h, shape->pad_h);
+    g.Wo = conv_out(shape->w, shape->s, shape->stride_w, shape->pad_w);
+    return run_contraction(g, plan, FAM_CONV, stream);
+}
+
+static int gemm_entry(const void *a, const void *b, const void *bias, void *c, const tt_gemm_shape *shape, int cls,
+                      const tt_schedule *sched, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!a || !b || !c || !shape) return TT_ERR_BAD_ARG;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(bias)) return TT_ERR_BAD_ARG;
+    tt_plan plan;
+    const int rc = make_plan(sched, cls, shape, ws, ws_bytes, &plan);
+    if (rc != TT_OK) return rc;
+    ContractArgs g;
+    std::memset(&g, 0, sizeof g);
+    fill_common(g, plan, sched, cls, shape->dtype);
+    g.a = a;
+    g.b = b;
+    g.bias = bias;
+    g.out = c;
+    g.ws = static_cast<float *>(ws);
+    g.has_bias = bias != nullptr;
+    g.Ho = g.Wo = 1;
+    return run_contraction(g, plan, family_of(cls, shape->trans_b), stream);
+}
+
+extern "C" int tt_dense_bias_relu(const void *x, const void *w, const void *bias, void *y,
+                                  const tt_gemm_shape *shape, int cls, const tt_schedule *sched, void *ws,
+                                  size_t ws_bytes, void *stream)
+{
+    if (!is_dense_class(cls)) return TT_ERR_BAD_ARG;
+    return gemm_entry(x, w, bias, y, shape, cls, sched, ws, ws_bytes, stream);
+}
+
+extern "C" int tt_batch_matmul(const void *a, const void *b, void *c, const tt_gemm_shape *shape,
+                               const tt_schedule *sched, void *ws, size_t ws_bytes, void *stream)
+{
+    return gemm_entry(a, b, nullptr, c, shape, TT_BATCH_MATMUL, sched, ws, ws_bytes, stream);
+}
+
+extern "C" int tt_dwconv(const void *x, const void *w, const void *bias, void *y, const tt_conv_shape *shape,
+                         const tt_schedule *sched, void *stream)
+{
+    if (!x || !w || !y || !shape) return TT_ERR_BAD_ARG;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias)) return TT_ERR_BAD_ARG;
+    tt_plan plan;
+    const int rc = make_plan(sched, TT_DWCONV_BIAS_RELU6, shape, nullptr, 0, &plan);
+    if (rc != TT_OK) return rc;
+    if (shape->dtype != TT_F32 || shape->r != 3 || shape->s != 3) return TT_ERR_UNSUPPORTED;
+    DwArgs g;
+    std::memset(&g, 0, sizeof g);
+    g.x = static_cast<const float *>(x);
+    g.w = static_cast<const float *>(w);
+    g.bias = static_cast<const float *>(bias);
+    g.y = static_cast<float *>(y);
+    g.map = tile_map_of(plan);
+    g.planes = shape->n * shape->c;
+    g.C = shape->c;
+    g.H = shape->h;
+    g.W = shape->w;
+    g.Ho = plan.M;
+    g.Wo = plan.N;
+    g.stride_h = shape->stride_h;
+    g.stride_w = shape->stride_w;
+    g.pad_h = shape->pad_h;
+    g.pad_w = shape->pad_w;
+    g.wave_m = plan.wave_m;
+    g.wave_n = plan.wave_n;
+    g.eff_vec = plan.eff_vec_c;
+    g.stages = plan.stages;
+    g.unroll = plan.eff_unroll;
+    if (plan.sketch == TT_SK_DIRECT) return launch_dw_direct(g, plan.grid, stream);
+    return launch_dwconv(g, plan, stream);
+}
+
+extern "C" int tt_debug_tile_map(const tt_plan *plan, int32_t *out_dev, void *stream)
+{
+    if (!plan || !out_dev || plan->status != TT_OK || plan->sketch == TT_SK_DIRECT || plan->grid < 1)
+        return TT_ERR_BAD_ARG;
+    return launch_tile_map_dump(tile_map_of(*plan), out_dev, stream);
+}
+
+// ---- standalone timing of one (kernel, schedule) pair (Section 4.3: pairs run as distinct programs) ----------
+
+namespace {
+
+int launch_kernel_desc(const tt_kernel_desc &k, const tt_schedule *sched, void *stream)
+{
+    if (is_conv_class(k.cls))
+        return tt_conv2d_bias_relu(k.bufs[0], k.bufs[1], k.bufs[2], k.bufs[3], k.bufs[4],
+                                   static_cast<const tt_conv_shape *>(k.shape), k.cls, sched, k.ws, k.ws_bytes, stream);
+    if (is_dense_class(k.cls))
+        return tt_dense_bias_relu(k.bufs[0], k.bufs[1], k.bufs[2], k.bufs[3],
+                                  static_cast<const tt_gemm_shape *>(k.shape), k.cls, sched, k.ws, k.ws_bytes, stream);
+    if (k.cls == TT_BATCH_MATMUL)
+        return tt_batch_matmul(k.bufs[0], k.bufs[1], k.bufs[2], static_cast<const tt_gemm_shape *>(k.shape), sched,
+                               k.ws, k.ws_bytes, stream);
+    if (k.cls == TT_DWCONV_BIAS_RELU6)
+        return tt_dwconv(k.bufs[0], k.bufs[1], k.bufs[2], k.bufs[3], static_cast<const tt_conv_shape *>(k.shape), sched,
+                         stream);
+    return TT_ERR_BAD_ARG;
+}
+
+struct Timer {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    bool ok = false;
+    Timer() { ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess; }
+    ~Timer()
+    {
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    }
+};
+
+tt_sweep_opts resolve(const tt_sweep_opts *o)
+{
+    tt_sweep_opts r;
+    r.warmup = 3;
+    r.samples = 10;
+    r.min_sample_us = 200;
+    r.max_launches = 64;
+    r.flags = 0;
+    r.allow_slower_than_default = 0;
+    if (o) {
+        if (o->warmup >= 0) r.warmup = o->warmup;
+        if (o->samples > 0) r.samples = o->samples;
+        if (o->min_sample_us > 0) r.min_sample_us = o->min_sample_us;
+        if (o->max_launches > 0) r.max_launches = o->max_launches;
+        r.flags = o->flags;
+        r.allow_slower_than_default = o->allow_slower_than_default;
+    }
+    return r;
+}
+
+int time_pair(const tt_kernel_desc &k, const tt_schedule *sched, const tt_sweep_opts &o, hipStream_t s, Timer &t,
+              double *median_us, double *min_us)
+{
+    // Validity first: nothing is launched for a record that does not apply.
+    tt_schedule def;
+    const tt_schedule *rec = sched;
+    if (!rec) {
+        const int rc = tt_schedule_default(k.cls, k.shape, &def);
+        if (rc != TT_OK) return rc;
+        rec = &def;
+    }
+    tt_plan plan;
+    int rc = tt_schedule_apply(rec, k.cls, k.shape, o.flags, &plan);
+    if (rc != TT_OK) return rc;
+    for (int i = 0; i < std::max(1, o.warmup); ++i) {
+        rc = launch_kernel_desc(k, rec, s);
+        if (rc != TT_OK) return rc;
+    }
+    // Size a sample: time one launch, then batch enough launches to fill min_sample_us.
+    float ms = 0.0f;
+    if (hipEventRecord(t.e0, s) != hipSuccess) return TT_ERR_HIP;
+    rc = launch_kernel_desc(k, rec, s);
+    if (rc != TT_OK) return rc;
+    if (hipEventRecord(t.e1, s) != hipSuccess || hipEventSynchronize(t.e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, t.e0, t.e1) != hipSuccess)
+        return TT_ERR_HIP;
+    const double one_us = std::max(1.0, (double)ms * 1000.0);
+    const int launches = (int)std::min<double>(o.max_launches, std::max(1.0, o.min_sample_us / one_us + 0.999));
+    std::vector<double> us(o.samples);
+    for (int smp = 0; smp < o.samples; ++smp) {
+        if (hipEventRecord(t.e0, s) != hipSuccess) return TT_ERR_HIP;
+        for (int l = 0; l < launches; ++l) {
+            rc = launch_kernel_desc(k, rec, s);
+            if (rc != TT_OK) return rc;
+        }
+        if (hipEventRecord(t.e1, s) != hipSuccess || hipEventSynchronize(t.e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, t.e0, t.e1) != hipSuccess)
+            return TT_ERR_HIP;
+        us[smp] = (double)ms * 1000.0 / launches;
+    }
+    std::sort(us.begin(), us.end());
+    const int n = (int)us.size();
+    if (median_us) *median_us = n % 2 ? us[n / 2] : 0.5 * (us[n / 2 - 1] + us[n / 2]);
+    if (min_us) *min_us = us[0];
+    return TT_OK;
+}
+
+} // namespace
+
+extern "C" int tt_time_pair(const tt_kernel_desc *kernel, const tt_schedule *sched, const tt_sweep_opts *opts,
+                            void *stream, double *median_us, double *min_us)
+{
+    if (!kernel || !kernel->shape) return TT_ERR_BAD_ARG;
+    Timer t;
+    if (!t.ok) return TT_ERR_HIP;
+    return time_pair(*kernel, sched, resolve(opts), static_cast<hipStream_t>(stream), t, median_us, min_us);
+}
+
+extern "C" int tt_transfer_sweep(const tt_kernel_desc *kernels, int nk, const tt_schedule *pool, int np,
+                                 const tt_sweep_opts *opts, void *stream, tt_sweep_row *rows, double *pair_us,
+                                 int64_t *evaluations, double *wall_seconds)
+{
+    if (nk < 0 || np < 0 || (nk && (!kernels || !rows)) || (np && !pool)) return TT_ERR_BAD_ARG;
+    const auto t0 = std::chrono::steady_clock::now();
+    const tt_sweep_opts o = resolve(opts);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timer timer;
+    if (!timer.ok) return TT_ERR_HIP;
+    std::vector<double> local((size_t)nk * np, -2.0), defaults(nk, 0.0);
+    std::vector<int32_t> kcls(nk), pcls(np);
+    for (int p = 0; p < np; ++p) pcls[p] = pool[p].cls;
+    int64_t evals = 0;
+    for (int k = 0; k < nk; ++k) {
+        if (!kernels[k].shape) return TT_ERR_BAD_ARG;
+        kcls[k] = kernels[k].cls;
+        // the default ("untuned") schedule is always evaluated: it is the baseline and the fallback
+        int rc = time_pair(kernels[k], nullptr, o, s, timer, &defaults[k], nullptr);
+        if (rc != TT_OK) return rc;
+        ++evals;
+        for (int p = 0; p < np; ++p) {
+            if (pool[p].cls != kernels[k].cls) continue; // other classes are never tried (Section 4.2)
+            ++evals;
+            double us = -1.0;
+            rc = time_pair(kernels[k], &pool[p], o, s, timer, &us, nullptr);
+            if (rc == TT_ERR_HIP) return rc;
+            // every other failure means "this record does not fit this kernel": the paper's -1
+            local[(size_t)k * np + p] = rc == TT_OK ? us : -1.0;
+        }
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) return TT_ERR_HIP;
+    const int rc = tt_sweep_select(kcls.data(), nk, pcls.data(), np, local.data(), defaults.data(),
+                                   o.allow_slower_than_default, rows);
+    if (rc != TT_OK) return rc;
+    if (pair_us) std::copy(local.begin(), local.end(), pair_us);
+    if (evaluations) *evaluations = evals;
+    if (wall_seconds) *wall_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return TT_OK;
+}

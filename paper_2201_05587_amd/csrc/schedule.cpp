@@ -1,0 +1,467 @@
+// Host-side schedule logic: default records, re-application of a record to a
+// target kernel (paper Sections 4.1, 4.2), the host mirror of the index map,
+// the selection rule of the sweep (Section 4.3) and the enumerated space.
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+#include "tt_internal.h"
+
+namespace tt {
+
+namespace {
+
+struct Extents {
+    int batch, M, N, K;
+};
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+inline bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+inline int pow2_floor(int v)
+{
+    int p = 1;
+    while (p <= v / 2) p <<= 1;
+    return p;
+}
+// Vector-width reformulation: the widest power of two not above vmax that divides the extent.
+inline int widest_dividing(int vmax, int64_t extent)
+{
+    int v = 1;
+    while (v * 2 <= vmax && extent % (v * 2) == 0) v *= 2;
+    return v;
+}
+inline int conv_out(int in, int f, int stride, int pad) { return (in + 2 * pad - f) / stride + 1; }
+
+bool extents_of(int cls, const void *shape, Extents *e, int *dtype)
+{
+    if (is_conv_class(cls) || cls == TT_DWCONV_BIAS_RELU6) {
+        const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
+        if (s->n < 1 || s->c < 1 || s->h < 1 || s->w < 1 || s->k < 1 || s->r < 1 || s->s < 1) return false;
+        if (s->stride_h < 1 || s->stride_w < 1 || s->pad_h < 0 || s->pad_w < 0) return false;
+        if (s->h + 2 * s->pad_h < s->r || s->w + 2 * s->pad_w < s->s) return false;
+        const int ho = conv_out(s->h, s->r, s->stride_h, s->pad_h);
+        const int wo = conv_out(s->w, s->s, s->stride_w, s->pad_w);
+        *dtype = s->dtype;
+        if (cls == TT_DWCONV_BIAS_RELU6) {
+            if (s->k != s->c) return false;
+            const int64_t planes = (int64_t)s->n * s->c;
+            if (planes > INT32_MAX) return false;
+            *e = {1, ho, wo, (int)planes};
+            return true;
+        }
+        const int64_t m = (int64_t)s->n * ho * wo, k = (int64_t)s->c * s->r * s->s;
+        if (m > INT32_MAX || k > INT32_MAX) return false;
+        *e = {1, (int)m, s->k, (int)k};
+        return true;
+    }
+    const tt_gemm_shape *g = static_cast<const tt_gemm_shape *>(shape);
+    if (g->batch < 1 || g->m < 1 || g->n < 1 || g->k < 1) return false;
+    if (g->trans_b != 0 && g->trans_b != 1) return false;
+    if (is_dense_class(cls) && (g->batch != 1 || g->trans_b != 1)) return false;
+    *dtype = g->dtype;
+    *e = {g->batch, g->m, g->n, g->k};
+    return true;
+}
+
+bool record_well_formed(const tt_schedule &r)
+{
+    if (r.cls < 0 || r.cls >= TT_NUM_CLASSES) return false;
+    if (r.sketch < TT_SK_MFMA || r.sketch > TT_SK_DIRECT) return false;
+    if (r.split_k < 1 || r.order < 0 || r.order >= 6) return false;
+    if (r.vec != 1 && r.vec != 2 && r.vec != 4 && r.vec != 8) return false;
+    if (r.unroll < 1 || (r.stages != 1 && r.stages != 2)) return false;
+    switch (r.sketch) {
+    case TT_SK_MFMA: {
+        if (r.mfma != 16 && r.mfma != 32) return false;
+        if (!pow2(r.tile_m) || !pow2(r.tile_n)) return false;
+        if (r.tile_m < 16 || r.tile_m > 256 || r.tile_n < 16 || r.tile_n > 256) return false;
+        if (r.tile_k != 16 && r.tile_k != 32 && r.tile_k != 64 && r.tile_k != 128) return false;
+        if (r.wave_m < r.mfma || r.wave_n < r.mfma) return false;
+        if (r.tile_m % r.wave_m || r.tile_n % r.wave_n || r.wave_m % r.mfma || r.wave_n % r.mfma) return false;
+        const int waves = (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
+        if (!pow2(waves) || waves > 16) return false;
+        return r.wave_m * r.wave_n / 64 <= 256;
+    }
+    case TT_SK_GEMV: {
+        if (r.mfma != 0 || r.split_k != 1) return false;
+        if (r.tile_m < 1 || r.tile_m > 8 || r.wave_m != r.tile_m) return false;
+        if (r.wave_n < 1 || r.wave_n > 8 || r.tile_n % r.wave_n) return false;
+        const int waves = r.tile_n / r.wave_n;
+        if (!pow2(waves) || waves > 16) return false;
+        if (r.tile_k % 64) return false;
+        const int chunk = r.tile_k / 64;
+        return chunk == 1 || chunk == 2 || chunk == 4 || chunk == 8;
+    }
+    case TT_SK_DWCONV: {
+        if (r.mfma != 0 || r.split_k != 1) return false;
+        if (r.tile_m < 1 || r.tile_n < 1 || r.tile_k < 1 || r.wave_m < 1 || r.wave_n < 1) return false;
+        if (r.tile_m % r.wave_m || r.tile_n % r.wave_n || r.wave_m > 8 || r.wave_n > 8) return false;
+        const int64_t threads = (int64_t)r.tile_k * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
+        return threads % 64 == 0 && threads >= 64 && threads <= 1024;
+    }
+    default:
+        return r.mfma == 0 && r.tile_m == 1 && r.tile_n == 1 && r.tile_k == 1 && r.wave_m == 1 && r.wave_n == 1 &&
+               r.split_k == 1;
+    }
+}
+
+int fail(tt_plan *plan, int status, int reason)
+{
+    std::memset(plan, 0, sizeof *plan);
+    plan->status = status;
+    plan->reason = reason;
+    plan->variant_id = -1;
+    return status;
+}
+
+tt_schedule make_record(int cls, int sketch, int tm, int tn, int tk, int wm, int wn, int mf, int split_k, int order,
+                        int vec, int unroll, int stages)
+{
+    tt_schedule r;
+    std::memset(&r, 0, sizeof r);
+    r.cls = cls;
+    r.sketch = sketch;
+    r.tile_m = tm;
+    r.tile_n = tn;
+    r.tile_k = tk;
+    r.wave_m = wm;
+    r.wave_n = wn;
+    r.mfma = mf;
+    r.split_k = split_k;
+    r.order = order;
+    r.vec = vec;
+    r.unroll = unroll;
+    r.stages = stages;
+    r.id = -1;
+    return r;
+}
+
+} // namespace
+
+int family_of(int cls, int trans_b)
+{
+    if (is_conv_class(cls)) return FAM_CONV;
+    if (cls == TT_BATCH_MATMUL && !trans_b) return FAM_GEMM_NN;
+    return FAM_GEMM_TN;
+}
+
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf)
+{
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.dtype == dtype && v.family == family && v.tile_m == tm && v.tile_n == tn && v.tile_k == tk &&
+            v.wave_m == wm && v.wave_n == wn && v.mfma == mf)
+            return i;
+    }
+    return -1;
+}
+
+} // namespace tt
+
+using namespace tt;
+
+extern "C" int tt_version(void) { return 100; }
+
+extern "C" const char *tt_status_name(int status)
+{
+    switch (status) {
+    case TT_OK: return "TT_OK";
+    case TT_ERR_INVALID_SCHEDULE: return "TT_ERR_INVALID_SCHEDULE";
+    case TT_ERR_CLASS_MISMATCH: return "TT_ERR_CLASS_MISMATCH";
+    case TT_ERR_BAD_ARG: return "TT_ERR_BAD_ARG";
+    case TT_ERR_WORKSPACE: return "TT_ERR_WORKSPACE";
+    case TT_ERR_UNSUPPORTED: return "TT_ERR_UNSUPPORTED";
+    case TT_ERR_HIP: return "TT_ERR_HIP";
+    default: return "TT_ERR_UNKNOWN";
+    }
+}
+
+extern "C" int tt_schedule_default(int cls, const void *shape, tt_schedule *out)
+{
+    if (!shape || !out || cls < 0 || cls >= TT_NUM_CLASSES) return TT_ERR_BAD_ARG;
+    Extents e;
+    int dt;
+    if (!extents_of(cls, shape, &e, &dt) || (dt != TT_F32 && dt != TT_BF16)) return TT_ERR_BAD_ARG;
+    const tt_schedule direct = make_record(cls, TT_SK_DIRECT, 1, 1, 1, 1, 1, 0, 1, 0, 1, 1, 1);
+    *out = direct;
+    if (cls == TT_DWCONV_BIAS_RELU6) {
+        if (dt != TT_F32) return TT_OK;
+        const int tn = std::min(32, pow2_floor(e.N)), tm = std::min(8, pow2_floor(e.M));
+        const int per_plane = tm * tn;
+        const int tk = std::max(1, 256 / per_plane);
+        if (tk > e.K || (tk * per_plane) % 64 || tk * per_plane < 64) return TT_OK;
+        *out = make_record(cls, TT_SK_DWCONV, tm, tn, tk, 1, 1, 0, 1, 0, 1, 1, 1);
+        return TT_OK;
+    }
+    const int kmin = dt == TT_F32 ? 16 : 32;
+    if (e.M >= 16 && e.N >= 16 && e.K >= kmin) {
+        const int tm = std::min(64, pow2_floor(e.M)), tn = std::min(64, pow2_floor(e.N));
+        *out = make_record(cls, TT_SK_MFMA, tm, tn, kmin, std::min(tm, 32), std::min(tn, 32), 16, 1, 0,
+                           dt == TT_F32 ? 4 : 8, 1, 2);
+        return TT_OK;
+    }
+    if (is_dense_class(cls) && e.K >= 64 && e.N >= 4)
+        *out = make_record(cls, TT_SK_GEMV, 1, 4, e.K >= 256 ? 256 : 64, 1, 1, 0, 1, 0, 4, 1, 1);
+    return TT_OK;
+}
+
+extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *shape, int flags, tt_plan *plan)
+{
+    if (!plan) return TT_ERR_BAD_ARG;
+    if (!sched || !shape || cls < 0 || cls >= TT_NUM_CLASSES || !record_well_formed(*sched))
+        return fail(plan, TT_ERR_BAD_ARG, TT_R_NONE);
+    Extents e;
+    int dt;
+    if (!extents_of(cls, shape, &e, &dt) || (dt != TT_F32 && dt != TT_BF16))
+        return fail(plan, TT_ERR_BAD_ARG, TT_R_NONE);
+    const tt_schedule &r = *sched;
+    // A record of another class would transform loops this kernel does not have (Section 4.2).
+    if (r.cls != cls) return fail(plan, TT_ERR_CLASS_MISMATCH, TT_R_NONE);
+    const bool dw = cls == TT_DWCONV_BIAS_RELU6;
+    if (r.sketch != TT_SK_DIRECT && (r.sketch == TT_SK_DWCONV) != dw)
+        return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_SKETCH_CLASS);
+    if (r.sketch == TT_SK_GEMV && !is_dense_class(cls)) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_SKETCH_CLASS);
+
+    const bool strict = (flags & TT_STRICT_DIVISIBLE) != 0;
+    const int elem = dt == TT_F32 ? 4 : 2;
+    const int vmax = std::min(r.vec, 16 / elem);
+    tt_plan p;
+    std::memset(&p, 0, sizeof p);
+    p.variant_id = -1;
+    p.sketch = r.sketch;
+    p.batch = e.batch;
+    p.M = e.M;
+    p.N = e.N;
+    p.K = e.K;
+    p.order = r.order;
+    p.stages = r.stages;
+    p.mfma = r.mfma;
+
+    if (r.sketch == TT_SK_DIRECT) {
+        const int64_t total = (int64_t)e.batch * e.M * e.N * (dw ? e.K : 1);
+        const int64_t grid = (total + 255) / 256;
+        if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+        p.tile_m = p.tile_n = p.tile_k = p.wave_m = p.wave_n = 1;
+        p.tiles_m = e.M;
+        p.tiles_n = e.N;
+        p.k_tiles = e.K;
+        p.tail_m = p.tail_n = p.tail_k = 1;
+        p.eff_split_k = 1;
+        p.k_iters = dw ? 1 : e.K;
+        p.slabs = dw ? e.K : e.batch;
+        p.eff_vec_a = p.eff_vec_b = p.eff_vec_c = p.eff_unroll = 1;
+        p.grid = (int)grid;
+        p.block = 256;
+        *plan = p;
+        return TT_OK;
+    }
+
+    // Inner factors are kept as recorded; a factor larger than the loop it splits cannot be applied.
+    const int factor[3] = {r.tile_m, r.tile_n, r.tile_k};
+    const int extent[3] = {e.M, e.N, e.K};
+    for (int i = 0; i < 3; ++i) {
+        if (factor[i] > extent[i]) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_FACTOR_GT_M + i);
+        if (strict && extent[i] % factor[i]) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_NOT_DIVISIBLE);
+    }
+    // Outer extents come from the target shape; the last tile is guarded.
+    p.tile_m = r.tile_m;
+    p.tile_n = r.tile_n;
+    p.tile_k = r.tile_k;
+    p.wave_m = r.wave_m;
+    p.wave_n = r.wave_n;
+    p.tiles_m = cdiv(e.M, r.tile_m);
+    p.tiles_n = cdiv(e.N, r.tile_n);
+    p.k_tiles = cdiv(e.K, r.tile_k);
+    p.tail_m = e.M - (p.tiles_m - 1) * r.tile_m;
+    p.tail_n = e.N - (p.tiles_n - 1) * r.tile_n;
+    p.tail_k = e.K - (p.k_tiles - 1) * r.tile_k;
+
+    if (r.sketch == TT_SK_DWCONV) {
+        const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
+        int64_t lds = 0;
+        if (r.stages == 2) {
+            const int64_t rows = (int64_t)(r.tile_m - 1) * s->stride_h + s->r;
+            const int64_t cols = (int64_t)(r.tile_n - 1) * s->stride_w + s->s;
+            lds = r.tile_k * rows * cols * elem;
+        }
+        if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
+        const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.k_tiles;
+        if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+        const int ev = widest_dividing(std::min(vmax, r.wave_n), e.N);
+        p.eff_split_k = 1;
+        p.k_iters = 1;
+        p.slabs = p.k_tiles;
+        p.eff_vec_a = ev;
+        p.eff_vec_b = 1;
+        p.eff_vec_c = ev;
+        p.eff_unroll = std::min(r.unroll, r.wave_m);
+        p.grid = (int)grid;
+        p.block = r.tile_k * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
+        p.lds_bytes = (int)lds;
+        *plan = p;
+        return TT_OK;
+    }
+
+    if (r.sketch == TT_SK_GEMV) {
+        const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * e.batch;
+        if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+        const int ev = widest_dividing(std::min(vmax, r.tile_k / 64), e.K);
+        p.eff_split_k = 1;
+        p.k_iters = p.k_tiles;
+        p.slabs = e.batch;
+        p.eff_vec_a = p.eff_vec_b = ev;
+        p.eff_vec_c = 1;
+        p.eff_unroll = std::min(r.unroll, p.k_tiles);
+        p.grid = (int)grid;
+        p.block = 64 * (r.tile_n / r.wave_n);
+        *plan = p;
+        return TT_OK;
+    }
+
+    // Matrix-core sketch.
+    const int granule = dt == TT_F32 ? (r.mfma == 32 ? 8 : 16) : (r.mfma == 32 ? 16 : 32);
+    if (r.tile_k % granule) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_K_GRANULE);
+    if (r.split_k > p.k_tiles) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_SPLIT_K);
+    if (strict && p.k_tiles % r.split_k) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_NOT_DIVISIBLE);
+    p.k_iters = cdiv(p.k_tiles, r.split_k);
+    p.eff_split_k = cdiv(p.k_tiles, p.k_iters);
+    const int64_t lds = (int64_t)r.stages * (r.tile_m + r.tile_n) * (r.tile_k + 16 / elem) * elem;
+    if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
+    int trans_b = 1;
+    if (is_conv_class(cls)) {
+        const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
+        const int ho = conv_out(s->h, s->r, s->stride_h, s->pad_h), wo = conv_out(s->w, s->s, s->stride_w, s->pad_w);
+        const bool pointwise = s->r == 1 && s->s == 1 && s->pad_h == 0 && s->pad_w == 0 && s->stride_h == 1 &&
+                               s->stride_w == 1;
+        p.eff_vec_a = pointwise ? widest_dividing(vmax, (int64_t)s->h * s->w)
+                                : (s->stride_w == 1 ? widest_dividing(vmax, wo) : 1);
+        p.eff_vec_b = widest_dividing(vmax, e.K);
+        p.eff_vec_c = widest_dividing(vmax, (int64_t)ho * wo);
+    } else {
+        trans_b = static_cast<const tt_gemm_shape *>(shape)->trans_b;
+        p.eff_vec_a = widest_dividing(vmax, e.K);
+        p.eff_vec_b = trans_b ? widest_dividing(vmax, e.K) : widest_dividing(vmax, e.N);
+        p.eff_vec_c = widest_dividing(vmax, e.N);
+    }
+    p.slabs = e.batch * p.eff_split_k;
+    const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.slabs;
+    if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+    p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
+    p.grid = (int)grid;
+    p.block = 64 * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
+    p.lds_bytes = (int)lds;
+    p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
+    p.variant_id = find_variant(dt, family_of(cls, trans_b), r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma);
+    *plan = p;
+    return TT_OK;
+}
+
+extern "C" int tt_plan_tile(const tt_plan *plan, int64_t wg, int32_t out[8])
+{
+    if (!plan || !out || plan->status != TT_OK || plan->sketch == TT_SK_DIRECT) return TT_ERR_BAD_ARG;
+    if (wg < 0 || wg >= plan->grid) return TT_ERR_BAD_ARG;
+    const TileCoord c = decode_tile(tile_map_of(*plan), (int32_t)wg);
+    out[0] = c.hi;
+    out[1] = c.lo;
+    out[2] = c.m0;
+    out[3] = c.m_ext;
+    out[4] = c.n0;
+    out[5] = c.n_ext;
+    out[6] = c.k0;
+    out[7] = c.k_ext;
+    return TT_OK;
+}
+
+extern "C" int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t *pool_cls, int np,
+                               const double *pair_us, const double *default_us, int allow_slower, tt_sweep_row *rows)
+{
+    if (nk < 0 || np < 0 || !rows || (nk && (!kernel_cls || !default_us)) || (np && (!pool_cls || !pair_us)))
+        return TT_ERR_BAD_ARG;
+    for (int k = 0; k < nk; ++k) {
+        tt_sweep_row row;
+        std::memset(&row, 0, sizeof row);
+        row.kernel = k;
+        row.chosen = -1;
+        row.default_us = default_us[k];
+        bool have = !allow_slower;
+        double best = default_us[k];
+        for (int p = 0; p < np; ++p) {
+            if (pool_cls[p] != kernel_cls[k]) {
+                ++row.n_other_class;
+                continue;
+            }
+            const double t = pair_us[(size_t)k * np + p];
+            if (t < 0) {
+                ++row.n_invalid; // does not apply to this kernel: skipped
+                continue;
+            }
+            ++row.n_valid;
+            if (!have || t < best) { // strict '<': the default, then the lowest index, win ties
+                best = t;
+                row.chosen = p;
+                have = true;
+            }
+        }
+        row.best_us = row.chosen < 0 ? default_us[k] : best;
+        rows[k] = row;
+    }
+    return TT_OK;
+}
+
+extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out, int cap)
+{
+    if (cls < 0 || cls >= TT_NUM_CLASSES || (dtype != TT_F32 && dtype != TT_BF16) || cap < 0 || (cap && !out))
+        return TT_ERR_BAD_ARG;
+    std::vector<tt_schedule> recs;
+    const int vfull = dtype == TT_F32 ? 4 : 8;
+    if (cls == TT_DWCONV_BIAS_RELU6) {
+        static const int tms[] = {1, 2, 4, 7, 8, 14, 16}, tns[] = {7, 8, 14, 16, 28, 32, 56, 64, 112};
+        static const int tks[] = {1, 2, 4, 8, 16}, wms[] = {1, 2, 4, 7}, wns[] = {1, 2, 4, 7};
+        for (int tm : tms)
+            for (int tn : tns)
+                for (int tk : tks)
+                    for (int wm : wms)
+                        for (int wn : wns)
+                            for (int stages = 1; stages <= (level >= 2 ? 2 : 1); ++stages) {
+                                tt_schedule r = make_record(cls, TT_SK_DWCONV, tm, tn, tk, wm, wn, 0, 1, 0, 4, wm, stages);
+                                if (record_well_formed(r)) recs.push_back(r);
+                            }
+    } else {
+        // families this class can run on: conv classes one, dense one, batch matmul both layouts
+        for (int i = 0; i < kNumVariants; ++i) {
+            const Variant &v = kVariants[i];
+            if (v.dtype != dtype) continue;
+            const bool fam_ok = is_conv_class(cls) ? v.family == FAM_CONV
+                                : cls == TT_BATCH_MATMUL ? (v.family == FAM_GEMM_TN || v.family == FAM_GEMM_NN)
+                                                         : v.family == FAM_GEMM_TN;
+            if (!fam_ok) continue;
+            // batch matmul records do not carry the layout: list each tile once (TN and NN tables are the same)
+            if (cls == TT_BATCH_MATMUL && v.family == FAM_GEMM_NN) continue;
+            static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 32};
+            const int n_split = level >= 1 ? 9 : 1;
+            const int n_order = level >= 2 ? 6 : (level >= 1 ? 2 : 1);
+            for (int si = 0; si < n_split; ++si)
+                for (int order = 0; order < n_order; ++order)
+                    for (int stages = (level >= 1 ? 1 : 2); stages <= 2; ++stages) {
+                        tt_schedule r = make_record(cls, TT_SK_MFMA, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n,
+                                                    v.mfma, splits[si], order, vfull, 8, stages);
+                        if (record_well_formed(r)) recs.push_back(r);
+                    }
+        }
+        if (is_dense_class(cls)) {
+            static const int tks[] = {64, 128, 256, 512};
+            for (int tm : {1, 2, 4})
+                for (int wn : {1, 2, 4})
+                    for (int waves : {1, 2, 4, 8})
+                        for (int tk : tks) {
+                            tt_schedule r = make_record(cls, TT_SK_GEMV, tm, wn * waves, tk, tm, wn, 0, 1, 0, 4, 1, 1);
+                            if (record_well_formed(r)) recs.push_back(r);
+                        }
+        }
+    }
+    for (size_t i = 0; i < recs.size(); ++i) {
+        recs[i].id = (int)i;
+        if ((int)i < cap) out[i] = recs[i];
+    }
+    return (int)recs.size();
+}

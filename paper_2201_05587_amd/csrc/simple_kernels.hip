@@ -1,0 +1,336 @@
+// Kernels that do not use the matrix cores: the one-thread-per-output "direct"
+// sketch (the unscheduled loop nest, always valid), the split-K reduction with
+// the fused epilogue, the wave-reduction GEMV sketch for small-M dense kernels,
+// the depthwise 3x3 tile kernel, and the index-map dump.
+#include <hip/hip_runtime.h>
+
+#include "contract.hip.h"
+#include "tt_internal.h"
+
+namespace tt {
+
+namespace {
+
+inline int launched()
+{
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : note_hip_error((int)e, "kernel launch");
+}
+
+// ---- direct sketch: one thread per output element ------------------------------------------------
+template <int DT, int FAM> __global__ void __launch_bounds__(256) direct_kernel(const ContractArgs g)
+{
+    using E = typename ElemOf<DT>::type;
+    const int64_t total = (int64_t)g.batch * g.M * g.N;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const E *a = static_cast<const E *>(g.a), *b = static_cast<const E *>(g.b);
+    float acc = 0.0f;
+    int n;
+    if constexpr (FAM == FAM_CONV) {
+        // idx walks the NCHW output: (img, n, p, q)
+        const int hw = g.Ho * g.Wo;
+        const int q = (int)(idx % g.Wo), p = (int)((idx / g.Wo) % g.Ho);
+        n = (int)((idx / hw) % g.N);
+        const int img = (int)(idx / ((int64_t)hw * g.N));
+        for (int c = 0; c < g.C; ++c)
+            for (int r = 0; r < g.R; ++r) {
+                const int ih = p * g.stride_h + r - g.pad_h;
+                if (ih < 0 || ih >= g.H) continue;
+                for (int s = 0; s < g.S; ++s) {
+                    const int iw = q * g.stride_w + s - g.pad_w;
+                    if (iw < 0 || iw >= g.W) continue;
+                    const float xv = load_as_float<DT>(a, (((int64_t)img * g.C + c) * g.H + ih) * g.W + iw);
+                    const float wv = load_as_float<DT>(b, (((int64_t)n * g.C + c) * g.R + r) * g.S + s);
+                    acc = fmaf(xv, wv, acc);
+                }
+            }
+    } else {
+        n = (int)(idx % g.N);
+        const int m = (int)((idx / g.N) % g.M);
+        const int bi = (int)(idx / ((int64_t)g.M * g.N));
+        const E *ar = a + ((int64_t)bi * g.M + m) * g.K;
+        const E *bb = b + (int64_t)bi * g.N * g.K;
+        for (int k = 0; k < g.K; ++k) {
+            const float bv = FAM == FAM_GEMM_TN ? load_as_float<DT>(bb, (int64_t)n * g.K + k)
+                                                : load_as_float<DT>(bb, (int64_t)k * g.N + n);
+            acc = fmaf(load_as_float<DT>(ar, k), bv, acc);
+        }
+    }
+    if (g.has_bias) acc += load_as_float<DT>(g.bias, n);
+    if (g.has_res) acc += load_as_float<DT>(g.res, idx);
+    store_from_float<DT>(g.out, idx, apply_act(acc, g.act));
+}
+
+// ---- split-K: sum the partial tiles in split order, then the fused epilogue -----------------------
+template <int DT, bool CONV> __global__ void __launch_bounds__(256) splitk_reduce_kernel(const ContractArgs g)
+{
+    const int64_t total = (int64_t)g.batch * g.M * g.N;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    float acc = 0.0f;
+    for (int z = 0; z < g.map.eff_split_k; ++z) acc += g.ws[(int64_t)z * total + idx];
+    const int n = CONV ? (int)((idx / ((int64_t)g.Ho * g.Wo)) % g.N) : (int)(idx % g.N);
+    if (g.has_bias) acc += load_as_float<DT>(g.bias, n);
+    if (g.has_res) acc += load_as_float<DT>(g.res, idx);
+    store_from_float<DT>(g.out, idx, apply_act(acc, g.act));
+}
+
+// ---- GEMV sketch: a wave owns WN outputs of TMR rows; lanes split K; butterfly reduction ---------
+template <int DT> __global__ void gemv_kernel(const ContractArgs g, int tile_m, int wave_n, int chunk)
+{
+    using E = typename ElemOf<DT>::type;
+    const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n_first = tc.n0 + wave * wave_n;
+    const E *x = static_cast<const E *>(g.a), *w = static_cast<const E *>(g.b);
+    const int ev = g.eff_vec_a;
+    float acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.0f;
+    const int step = 64 * chunk;
+    for (int kb = 0; kb < g.K; kb += step) {
+        const int k = kb + lane * chunk;
+        for (int c0 = 0; c0 < chunk; c0 += ev) {
+            // ev consecutive K per access; K % ev == 0 so a group is all in or all out
+            if (k + c0 >= g.K) break;
+            float xv[8][8], wv[8][8];
+            for (int i = 0; i < tile_m; ++i) {
+                const int m = tc.m0 + i;
+                for (int e = 0; e < ev; ++e)
+                    xv[i][e] = m < g.M ? load_as_float<DT>(x, (int64_t)m * g.K + k + c0 + e) : 0.0f;
+            }
+            for (int j = 0; j < wave_n; ++j) {
+                const int n = n_first + j;
+                for (int e = 0; e < ev; ++e)
+                    wv[j][e] = n < g.N ? load_as_float<DT>(w, (int64_t)n * g.K + k + c0 + e) : 0.0f;
+            }
+            for (int i = 0; i < tile_m; ++i)
+                for (int j = 0; j < wave_n; ++j)
+                    for (int e = 0; e < ev; ++e) acc[i][j] = fmaf(xv[i][e], wv[j][e], acc[i][j]);
+        }
+    }
+    for (int i = 0; i < tile_m; ++i)
+        for (int j = 0; j < wave_n; ++j) {
+            float v = acc[i][j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            const int m = tc.m0 + i, n = n_first + j;
+            if (lane == 0 && m < g.M && n < g.N && n < tc.n0 + tc.n_ext) {
+                if (g.has_bias) v += load_as_float<DT>(g.bias, n);
+                store_from_float<DT>(g.out, (int64_t)m * g.N + n, apply_act(v, g.act));
+            }
+        }
+}
+
+// ---- depthwise 3x3: (planes, rows, cols) tile per workgroup, WM x WN outputs per thread -----------
+// Threads are laid out cols fastest, then rows, then planes, so a wave reads and writes whole row
+// segments.  With two stages the input patch of the tile is first copied to LDS.
+template <int WM, int WN> __global__ void dwconv3x3_kernel(const DwArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    float *patch = reinterpret_cast<float *>(smem_raw);
+    const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
+    const int tcols = g.map.tile_n / WN, trows = g.map.tile_m / WM;
+    const int tid = threadIdx.x;
+    const int tx = tid % tcols, ty = (tid / tcols) % trows, tp = tid / (tcols * trows);
+    const int plane = tc.k0 + tp;
+    const int p0 = tc.m0 + ty * WM, q0 = tc.n0 + tx * WN;
+    const int prow = (g.map.tile_m - 1) * g.stride_h + 3, pcol = (g.map.tile_n - 1) * g.stride_w + 3;
+    const int ih_org = tc.m0 * g.stride_h - g.pad_h, iw_org = tc.n0 * g.stride_w - g.pad_w;
+    if (g.stages == 2) {
+        const int per_plane = prow * pcol, total = per_plane * g.map.tile_k;
+        for (int e = tid; e < total; e += blockDim.x) {
+            const int pl = e / per_plane, rem = e - pl * per_plane;
+            const int rr = rem / pcol, cc = rem - rr * pcol;
+            const int ih = ih_org + rr, iw = iw_org + cc;
+            float v = 0.0f;
+            if (pl < tc.k_ext && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+                v = g.x[((int64_t)(tc.k0 + pl) * g.H + ih) * g.W + iw];
+            patch[e] = v;
+        }
+        __syncthreads();
+    }
+    if (tp >= tc.k_ext) return;
+    const int ch = plane % g.C;
+    float wgt[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) wgt[i] = g.w[ch * 9 + i];
+    const float bias = g.bias ? g.bias[ch] : 0.0f;
+    const float *xp = g.x + (int64_t)plane * g.H * g.W;
+    float *yp = g.y + (int64_t)plane * g.Ho * g.Wo;
+    auto body = [&](int i) {
+        const int p = p0 + i;
+        if (p >= g.Ho || p >= tc.m0 + tc.m_ext) return;
+        float out[WN];
+#pragma unroll
+        for (int j = 0; j < WN; ++j) out[j] = bias;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int ih = p * g.stride_h + r - g.pad_h;
+#pragma unroll
+            for (int j = 0; j < WN; ++j) {
+#pragma unroll
+                for (int s = 0; s < 3; ++s) {
+                    const int iw = (q0 + j) * g.stride_w + s - g.pad_w;
+                    float v = 0.0f;
+                    if (g.stages == 2) {
+                        v = patch[(tp * prow + (ih - ih_org)) * pcol + (iw - iw_org)];
+                    } else if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
+                        v = xp[(int64_t)ih * g.W + iw];
+                    }
+                    out[j] = fmaf(v, wgt[r * 3 + s], out[j]);
+                }
+            }
+        }
+        const int qlim = min(g.Wo, tc.n0 + tc.n_ext);
+        if (WN == 4 && g.eff_vec == 4 && q0 + 3 < qlim) {
+            float4 o;
+            o.x = fminf(fmaxf(out[0], 0.0f), 6.0f);
+            o.y = fminf(fmaxf(out[1 % WN], 0.0f), 6.0f);
+            o.z = fminf(fmaxf(out[2 % WN], 0.0f), 6.0f);
+            o.w = fminf(fmaxf(out[3 % WN], 0.0f), 6.0f);
+            *reinterpret_cast<float4 *>(yp + (int64_t)p * g.Wo + q0) = o;
+        } else {
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+                if (q0 + j < qlim) yp[(int64_t)p * g.Wo + q0 + j] = fminf(fmaxf(out[j], 0.0f), 6.0f);
+        }
+    };
+    if (g.unroll >= WM) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) body(i);
+    } else {
+#pragma unroll 1
+        for (int i = 0; i < WM; ++i) body(i);
+    }
+}
+
+__global__ void __launch_bounds__(256) dw_direct_kernel(const DwArgs g)
+{
+    const int64_t total = (int64_t)g.planes * g.Ho * g.Wo;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int q = (int)(idx % g.Wo), p = (int)((idx / g.Wo) % g.Ho);
+    const int plane = (int)(idx / ((int64_t)g.Ho * g.Wo));
+    const int ch = plane % g.C;
+    float acc = 0.0f;
+    for (int r = 0; r < 3; ++r) {
+        const int ih = p * g.stride_h + r - g.pad_h;
+        if (ih < 0 || ih >= g.H) continue;
+        for (int s = 0; s < 3; ++s) {
+            const int iw = q * g.stride_w + s - g.pad_w;
+            if (iw < 0 || iw >= g.W) continue;
+            acc = fmaf(g.x[((int64_t)plane * g.H + ih) * g.W + iw], g.w[ch * 9 + r * 3 + s], acc);
+        }
+    }
+    if (g.bias) acc += g.bias[ch];
+    g.y[idx] = fminf(fmaxf(acc, 0.0f), 6.0f);
+}
+
+__global__ void __launch_bounds__(256) tile_map_dump_kernel(const TileMap map, int32_t *out)
+{
+    const int wg = blockIdx.x * 256 + threadIdx.x;
+    if (wg >= map.grid) return;
+    const TileCoord c = decode_tile(map, wg);
+    int32_t *o = out + (int64_t)wg * 8;
+    o[0] = c.hi;
+    o[1] = c.lo;
+    o[2] = c.m0;
+    o[3] = c.m_ext;
+    o[4] = c.n0;
+    o[5] = c.n_ext;
+    o[6] = c.k0;
+    o[7] = c.k_ext;
+}
+
+template <int DT> int launch_direct_dt(const ContractArgs &a, int family, int grid, hipStream_t s)
+{
+    switch (family) {
+    case FAM_CONV: hipLaunchKernelGGL((direct_kernel<DT, FAM_CONV>), dim3(grid), dim3(256), 0, s, a); break;
+    case FAM_GEMM_TN: hipLaunchKernelGGL((direct_kernel<DT, FAM_GEMM_TN>), dim3(grid), dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL((direct_kernel<DT, FAM_GEMM_NN>), dim3(grid), dim3(256), 0, s, a); break;
+    }
+    return launched();
+}
+
+} // namespace
+
+int launch_direct(const ContractArgs &args, int family, int grid, void *stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return args.dtype == TT_F32 ? launch_direct_dt<TT_F32>(args, family, grid, s)
+                                : launch_direct_dt<TT_BF16>(args, family, grid, s);
+}
+
+int launch_splitk_reduce(const ContractArgs &args, int family, void *stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t total = (int64_t)args.batch * args.M * args.N;
+    const int grid = (int)((total + 255) / 256);
+    if (family == FAM_CONV) {
+        if (args.dtype == TT_F32)
+            hipLaunchKernelGGL((splitk_reduce_kernel<TT_F32, true>), dim3(grid), dim3(256), 0, s, args);
+        else
+            hipLaunchKernelGGL((splitk_reduce_kernel<TT_BF16, true>), dim3(grid), dim3(256), 0, s, args);
+    } else {
+        if (args.dtype == TT_F32)
+            hipLaunchKernelGGL((splitk_reduce_kernel<TT_F32, false>), dim3(grid), dim3(256), 0, s, args);
+        else
+            hipLaunchKernelGGL((splitk_reduce_kernel<TT_BF16, false>), dim3(grid), dim3(256), 0, s, args);
+    }
+    return launched();
+}
+
+int launch_gemv(const ContractArgs &args, const tt_plan &plan, void *stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int chunk = plan.tile_k / 64;
+    if (args.dtype == TT_F32)
+        hipLaunchKernelGGL((gemv_kernel<TT_F32>), dim3(plan.grid), dim3(plan.block), 0, s, args, plan.tile_m,
+                           plan.wave_n, chunk);
+    else
+        hipLaunchKernelGGL((gemv_kernel<TT_BF16>), dim3(plan.grid), dim3(plan.block), 0, s, args, plan.tile_m,
+                           plan.wave_n, chunk);
+    return launched();
+}
+
+int launch_dwconv(const DwArgs &a, const tt_plan &plan, void *stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid(plan.grid), block(plan.block);
+    const int lds = plan.lds_bytes;
+#define TT_DW_CASE(WM_, WN_)                                                                                         \
+    if (a.wave_m == WM_ && a.wave_n == WN_) {                                                                        \
+        auto kern = dwconv3x3_kernel<WM_, WN_>;                                                                      \
+        if (lds > 48 * 1024 &&                                                                                       \
+            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                lds) != hipSuccess)                                                                  \
+            return TT_ERR_HIP;                                                                                       \
+        hipLaunchKernelGGL(kern, grid, block, lds, s, a);                                                            \
+        return launched();                                                                                           \
+    }
+    TT_DW_CASE(1, 1) TT_DW_CASE(1, 2) TT_DW_CASE(1, 4) TT_DW_CASE(1, 7)
+    TT_DW_CASE(2, 1) TT_DW_CASE(2, 2) TT_DW_CASE(2, 4) TT_DW_CASE(2, 7)
+    TT_DW_CASE(4, 1) TT_DW_CASE(4, 2) TT_DW_CASE(4, 4) TT_DW_CASE(4, 7)
+    TT_DW_CASE(7, 1) TT_DW_CASE(7, 2) TT_DW_CASE(7, 4) TT_DW_CASE(7, 7)
+#undef TT_DW_CASE
+    return TT_ERR_UNSUPPORTED;
+}
+
+int launch_dw_direct(const DwArgs &a, int grid, void *stream)
+{
+    hipLaunchKernelGGL(dw_direct_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    return launched();
+}
+
+int launch_tile_map_dump(const TileMap &map, int32_t *out_dev, void *stream)
+{
+    const int grid = (map.grid + 255) / 256;
+    hipLaunchKernelGGL(tile_map_dump_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), map, out_dev);
+    return launched();
+}
+
+} // namespace tt

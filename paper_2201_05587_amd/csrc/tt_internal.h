@@ -1,0 +1,181 @@
+// Internal declarations shared by the host code and the HIP kernels of libtt.
+#pragma once
+
+#include <stdint.h>
+
+#include "tt.h"
+
+#if defined(__HIPCC__)
+#include <hip/hip_runtime.h>
+#define TT_HD __host__ __device__ __forceinline__
+#else
+#define TT_HD inline
+#endif
+
+namespace tt {
+
+constexpr int kXcds = 8;           // accelerator complex dies; workgroups are dealt to them round-robin
+constexpr int kGroupM = 8;         // band height of raster order 2
+constexpr int kLdsBudget = 160 * 1024;
+
+enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
+
+// What a workgroup needs to find its tile: the integer fields of the plan the index map reads.
+struct TileMap {
+    int32_t sketch, order, grid;
+    int32_t tiles_m, tiles_n, tile_m, tile_n, tile_k;
+    int32_t M, N, K;
+    int32_t eff_split_k, k_iters, k_tiles;
+};
+
+struct TileCoord {
+    int32_t hi, lo;        // (batch, k-split); depthwise: (plane tile, 0)
+    int32_t m0, m_ext, n0, n_ext, k0, k_ext;
+};
+
+// Workgroup id -> tile.  One implementation for the host mirror (tt_plan_tile) and every kernel.
+TT_HD TileCoord decode_tile(const TileMap &p, int32_t wg)
+{
+    int32_t L = wg;
+    if (p.order >= 3) {
+        // XCD x receives workgroups x, x + 8, ...: give it one contiguous run of logical ids.
+        const int32_t per = p.grid / kXcds, rem = p.grid % kXcds;
+        const int32_t x = wg % kXcds, j = wg / kXcds;
+        L = x * per + (x < rem ? x : rem) + j;
+    }
+    const int32_t T = p.tiles_m * p.tiles_n;
+    const int32_t slab = L / T, t = L % T;
+    const int32_t base = p.order % 3;
+    int32_t im, in;
+    if (base == 0) {
+        im = t % p.tiles_m;
+        in = t / p.tiles_m;
+    } else if (base == 1) {
+        in = t % p.tiles_n;
+        im = t / p.tiles_n;
+    } else {
+        const int32_t width = kGroupM * p.tiles_n;
+        const int32_t first = (t / width) * kGroupM;
+        const int32_t left = p.tiles_m - first;
+        const int32_t gsize = left < kGroupM ? left : kGroupM;
+        im = first + (t % width) % gsize;
+        in = (t % width) / gsize;
+    }
+    TileCoord c;
+    c.m0 = im * p.tile_m;
+    c.n0 = in * p.tile_n;
+    c.m_ext = (p.M - c.m0) < p.tile_m ? (p.M - c.m0) : p.tile_m;
+    c.n_ext = (p.N - c.n0) < p.tile_n ? (p.N - c.n0) : p.tile_n;
+    if (p.sketch == TT_SK_DWCONV) {
+        c.hi = slab;
+        c.lo = 0;
+        c.k0 = slab * p.tile_k;
+        c.k_ext = (p.K - c.k0) < p.tile_k ? (p.K - c.k0) : p.tile_k;
+    } else if (p.sketch == TT_SK_GEMV) {
+        c.hi = slab;
+        c.lo = 0;
+        c.k0 = 0;
+        c.k_ext = p.K;
+    } else {
+        c.hi = slab / p.eff_split_k;
+        c.lo = slab % p.eff_split_k;
+        const int32_t kt0 = c.lo * p.k_iters;
+        int32_t kt1 = kt0 + p.k_iters;
+        if (kt1 > p.k_tiles) kt1 = p.k_tiles;
+        c.k0 = kt0 * p.tile_k;
+        const int32_t kend = kt1 * p.tile_k < p.K ? kt1 * p.tile_k : p.K;
+        c.k_ext = kend - c.k0;
+    }
+    return c;
+}
+
+inline TileMap tile_map_of(const tt_plan &pl)
+{
+    TileMap m;
+    m.sketch = pl.sketch;
+    m.order = pl.order;
+    m.grid = pl.grid;
+    m.tiles_m = pl.tiles_m;
+    m.tiles_n = pl.tiles_n;
+    m.tile_m = pl.tile_m;
+    m.tile_n = pl.tile_n;
+    m.tile_k = pl.tile_k;
+    m.M = pl.M;
+    m.N = pl.N;
+    m.K = pl.K;
+    m.eff_split_k = pl.eff_split_k;
+    m.k_iters = pl.k_iters;
+    m.k_tiles = pl.k_tiles;
+    return m;
+}
+
+// Operand families of the matrix-core contraction kernel.
+enum Family {
+    FAM_CONV = 0,    // A = NCHW activations gathered as an implicit GEMM, B = KCRS filters ([N][K])
+    FAM_GEMM_TN = 1, // A = [M][K], B = [N][K] (dense; batch matmul with trans_b = 1)
+    FAM_GEMM_NN = 2  // A = [M][K], B = [K][N] (batch matmul with trans_b = 0)
+};
+
+// Everything a contraction kernel (matrix-core, direct or split-K reduce) needs, passed by value.
+struct ContractArgs {
+    const void *a, *b, *bias, *res;
+    void *out;
+    float *ws;
+    TileMap map;
+    int32_t batch, M, N, K;
+    // convolution geometry (FAM_CONV)
+    int32_t C, H, W, R, S, stride_h, stride_w, pad_h, pad_w, Ho, Wo;
+    int32_t eff_vec_a, eff_vec_b, eff_vec_c, stages, unroll, act, has_bias, has_res, dtype;
+};
+
+struct DwArgs {
+    const float *x, *w, *bias;
+    float *y;
+    TileMap map;
+    int32_t planes, C, H, W, Ho, Wo, stride_h, stride_w, pad_h, pad_w;
+    int32_t wave_m, wave_n, eff_vec, stages, unroll;
+};
+
+struct Variant {
+    int32_t dtype, family, tile_m, tile_n, tile_k, wave_m, wave_n, mfma;
+    int (*launch)(const ContractArgs &args, int grid, int lds_bytes, void *stream);
+};
+
+// variant table (generated) and lookups
+extern const Variant kVariants[];
+extern const int kNumVariants;
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf);
+int family_of(int cls, int trans_b);
+
+// launchers of the non-matrix-core kernels (simple_kernels.hip)
+int launch_direct(const ContractArgs &args, int family, int grid, void *stream);
+int launch_splitk_reduce(const ContractArgs &args, int family, void *stream);
+int launch_gemv(const ContractArgs &args, const tt_plan &plan, void *stream);
+int launch_dwconv(const DwArgs &args, const tt_plan &plan, void *stream);
+int launch_dw_direct(const DwArgs &args, int grid, void *stream);
+int launch_tile_map_dump(const TileMap &map, int32_t *out_dev, void *stream);
+
+// Remember the text of a failed HIP call for tt_last_error(); returns TT_ERR_HIP.
+int note_hip_error(int hip_error_code, const char *where);
+
+inline int act_of_class(int cls)
+{
+    switch (cls) {
+    case TT_CONV2D_BIAS_RELU:
+    case TT_CONV2D_BIAS_ADD_RELU:
+    case TT_DENSE_BIAS_RELU:
+        return ACT_RELU;
+    case TT_CONV2D_BIAS_RELU6:
+    case TT_DWCONV_BIAS_RELU6:
+        return ACT_RELU6;
+    case TT_DENSE_BIAS_GELU:
+        return ACT_GELU;
+    default:
+        return ACT_NONE;
+    }
+}
+
+inline bool is_conv_class(int cls) { return cls >= TT_CONV2D_ADD && cls <= TT_CONV2D_BIAS_RELU6; }
+inline bool is_dense_class(int cls) { return cls >= TT_DENSE_ADD && cls <= TT_DENSE_BIAS_GELU; }
+
+} // namespace tt

@@ -1,0 +1,220 @@
+"""GPU parity: every operator class through the C-ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from oracle import schedule as S
+from paper_2201_05587_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2201_05587_amd import api as _api
+    return _api
+
+
+@pytest.fixture(scope="module")
+def P():
+    import parity
+    return parity
+
+
+def mfma(api, cls, tm, tn, tk, wm, wn, mf, split_k=1, order=0, vec=8, unroll=8, stages=2):
+    return api.make_schedule(cls, api.TT_SK_MFMA, tm, tn, tk, wm, wn, mf, split_k, order, vec, unroll, stages)
+
+
+def conv_kernel(cls, n, c, hw, k, f, stride, dtype=wl.F32, pad=None):
+    pad = f // 2 if pad is None else pad
+    return wl.Kernel(cls, wl.ConvShape(n, c, hw, hw, k, f, f, stride, stride, pad, pad, dtype), 1,
+                     f"conv{f}x{f}_{c}_{k}_{hw}_s{stride}")
+
+
+# ---- index map ------------------------------------------------------------------------------------
+def test_device_index_map_matches_oracle_bit_for_bit(api):
+    from test_host_schedule import to_c_record
+    from test_oracle_schedule import oshape
+    cases = [(wl.cfg1_target(), S.record(1, S.SK_MFMA, 32, 32, 32, 16, 16, 16, 4, o)) for o in range(6)]
+    cases += [(wl.resnet18_kernels()[13], S.record(1, S.SK_MFMA, 32, 64, 32, 32, 32, 32, 7, 5))]
+    cases += [(wl.bert_kernels()[5], S.record(7, S.SK_MFMA, 64, 64, 32, 32, 32, 16, 2, 2))]
+    cases += [(wl.mobilenetv2_kernels(2)[3], S.record(8, S.SK_DWCONV, 4, 16, 4, 1, 1, 0, 1, 4, 1, 1, 1))]
+    cases += [(wl.resnet50_kernels(32, wl.BF16, False)[0], S.record(1, S.SK_MFMA, 128, 64, 32, 64, 32, 32, 1, 5))]
+    for k, rec in cases:
+        oplan = S.apply(rec, k.cls, oshape(k))
+        assert oplan["status"] == S.OK
+        cplan = api.tt_schedule_apply(to_c_record(rec), k.cls, k.shape)
+        dev = api.tt_debug_tile_map(cplan)
+        want = np.array([S.plan_tile(oplan, wg) for wg in range(oplan["grid"])], dtype=np.int32)
+        np.testing.assert_array_equal(dev, want)
+
+
+# ---- conv2d classes, fp32 -------------------------------------------------------------------------
+def test_cfg1_conv_under_default_and_donor_tiles(api, P):
+    k = wl.cfg1_target()
+    E = k.cls
+    scheds = [None,
+              mfma(api, E, 32, 32, 16, 16, 16, 16), mfma(api, E, 64, 64, 32, 32, 32, 32),
+              mfma(api, E, 64, 32, 32, 32, 32, 16), mfma(api, E, 128, 64, 32, 64, 32, 32),
+              mfma(api, E, 256, 64, 16, 64, 64, 32, order=1), mfma(api, E, 32, 64, 32, 32, 32, 32, stages=1, unroll=1),
+              mfma(api, E, 64, 64, 16, 32, 32, 16, split_k=4, order=3), mfma(api, E, 16, 16, 32, 16, 16, 16, split_k=3),
+              api.make_schedule(E, api.TT_SK_DIRECT, 1, 1, 1, 1, 1, 0, 1, 0, 1, 1, 1)]
+    ref, outs = P.check_kernel(k, scheds)
+    assert ref.min() >= 0.0
+    # same (tile_k, split_k, block) => same summation order => identical bits, whatever the tile shape
+    a = P.run_gpu(__import__("paper_2201_05587_amd.harness", fromlist=["x"]).device_kernel(k, 1234),
+                  mfma(api, E, 64, 64, 32, 32, 32, 32))
+    np.testing.assert_array_equal(a, outs[2])
+
+
+@pytest.mark.parametrize("case", [
+    ("stem7x7", wl.CLS_CONV2D_BIAS_RELU, (1, 3, 224, 64, 7, 2)),
+    ("proj1x1s2", wl.CLS_CONV2D_ADD, (1, 64, 56, 128, 1, 2)),
+    ("res3x3", wl.CLS_CONV2D_BIAS_ADD_RELU, (1, 128, 28, 128, 3, 1)),
+    ("s2_3x3", wl.CLS_CONV2D_BIAS_RELU, (1, 128, 28, 256, 3, 2)),
+    ("map7x7", wl.CLS_CONV2D_BIAS_ADD_RELU, (1, 512, 7, 512, 3, 1)),
+    ("pw_relu6", wl.CLS_CONV2D_BIAS_RELU6, (2, 24, 56, 144, 1, 1)),
+    ("pw_small_n", wl.CLS_CONV2D_ADD, (1, 96, 112, 24, 1, 1)),
+    ("batch3_5x5", wl.CLS_CONV2D_BIAS_RELU, (3, 20, 19, 40, 5, 1)),
+])
+def test_conv_classes_and_shapes_fp32(api, P, case):
+    name, cls, (n, c, hw, kk, f, st) = case
+    k = conv_kernel(cls, n, c, hw, kk, f, st)
+    scheds = [None, mfma(api, cls, 32, 32, 16, 16, 16, 16, order=1), mfma(api, cls, 16, 16, 16, 16, 16, 16, split_k=2),
+              mfma(api, cls, 32, 16, 32, 32, 16, 16, order=5, stages=1)]
+    if k.gemm_extents()[1] >= 64 and k.gemm_extents()[2] >= 64:
+        scheds.append(mfma(api, cls, 64, 64, 32, 32, 32, 32, split_k=2, order=2))
+    P.check_kernel(k, scheds)
+
+
+def test_conv_bf16(api, P):
+    for cls, dims in ((wl.CLS_CONV2D_BIAS_RELU, (2, 64, 28, 128, 3, 1)), (wl.CLS_CONV2D_BIAS_ADD_RELU, (2, 128, 14, 64, 1, 1)),
+                      (wl.CLS_CONV2D_ADD, (2, 64, 28, 96, 1, 2)), (wl.CLS_CONV2D_BIAS_RELU, (1, 3, 64, 32, 7, 2))):
+        k = conv_kernel(cls, *dims, dtype=wl.BF16)
+        scheds = [None, mfma(api, cls, 32, 32, 32, 16, 16, 16), mfma(api, cls, 64, 64, 64, 32, 32, 32, split_k=2),
+                  mfma(api, cls, 64, 32, 32, 32, 32, 32, order=4, stages=1, unroll=1)]
+        P.check_kernel(k, scheds)
+
+
+# ---- dense / batch matmul -------------------------------------------------------------------------
+def test_dense_classes(api, P):
+    for cls in (wl.CLS_DENSE_ADD, wl.CLS_DENSE_BIAS_RELU, wl.CLS_DENSE_BIAS_GELU):
+        for dt in (wl.F32, wl.BF16):
+            k = wl.Kernel(cls, wl.GemmShape(1, 200, 264, 328, 1, dt), 1, f"dense_{cls}_{dt}")
+            tk = 16 if dt == wl.F32 else 32
+            scheds = [None, mfma(api, cls, 64, 64, tk * 2, 32, 32, 32), mfma(api, cls, 32, 32, tk, 16, 16, 16, split_k=3),
+                      mfma(api, cls, 128, 128, tk, 64, 64, 32, order=1),
+                      api.make_schedule(cls, api.TT_SK_DIRECT, 1, 1, 1, 1, 1, 0, 1, 0, 1, 1, 1)]
+            P.check_kernel(k, scheds)
+
+
+def test_dense_odd_k_uses_narrow_loads(api, P):
+    for dt, kdim in ((wl.F32, 147), (wl.BF16, 150), (wl.BF16, 148), (wl.F32, 150)):
+        k = wl.Kernel(wl.CLS_DENSE_BIAS_RELU, wl.GemmShape(1, 70, 90, kdim, 1, dt), 1, f"dense_k{kdim}")
+        tk = 16 if dt == wl.F32 else 32
+        P.check_kernel(k, [None, mfma(api, k.cls, 32, 32, tk, 16, 16, 16, vec=8), mfma(api, k.cls, 32, 32, tk, 16, 16, 16, vec=2)])
+
+
+def test_gemv_sketch_resnet_classifier(api, P):
+    k = wl.resnet18_kernels()[-1]
+    assert k.gemm_extents() == (1, 1, 1000, 512)
+    gemv = lambda tm, tn, wn, tk, vec: api.make_schedule(k.cls, api.TT_SK_GEMV, tm, tn, tk, tm, wn, 0, 1, 0, vec, 1, 1)
+    P.check_kernel(k, [None, gemv(1, 4, 1, 256, 4), gemv(1, 8, 2, 512, 4), gemv(1, 16, 4, 64, 1), gemv(1, 2, 2, 128, 2)])
+    k4 = wl.Kernel(wl.CLS_DENSE_BIAS_GELU, wl.GemmShape(1, 5, 70, 200, 1, wl.BF16), 1, "gemv_bf16")
+    gemv4 = lambda tm, tn, wn, tk, vec: api.make_schedule(k4.cls, api.TT_SK_GEMV, tm, tn, tk, tm, wn, 0, 1, 0, vec, 1, 1)
+    P.check_kernel(k4, [None, gemv4(2, 8, 2, 128, 8), gemv4(4, 4, 4, 64, 1)])
+
+
+def test_batch_matmul_both_layouts(api, P):
+    for trans_b in (1, 0):
+        for dt in (wl.BF16, wl.F32):
+            k = wl.Kernel(wl.CLS_BATCH_MATMUL, wl.GemmShape(5, 128, 72, 96, trans_b, dt), 1, f"bmm_t{trans_b}_{dt}")
+            tk = 16 if dt == wl.F32 else 32
+            scheds = [None, mfma(api, k.cls, 64, 64, tk, 32, 32, 32), mfma(api, k.cls, 32, 32, tk * 2, 16, 16, 16, split_k=2, order=4),
+                      api.make_schedule(k.cls, api.TT_SK_DIRECT, 1, 1, 1, 1, 1, 0, 1, 0, 1, 1, 1)]
+            P.check_kernel(k, scheds)
+
+
+def test_bert_shaped_kernels_bf16(api, P):
+    for k in wl.bert_kernels(seq=128, batch=2):
+        scheds = [None, mfma(api, k.cls, 128, 128, 64, 64, 64, 32), mfma(api, k.cls, 64, 64, 32, 32, 32, 16, split_k=2)]
+        if k.gemm_extents()[2] < 128:
+            scheds[1] = mfma(api, k.cls, 64, 64, 64, 32, 32, 32)
+        P.check_kernel(k, scheds)
+
+
+# ---- depthwise --------------------------------------------------------------------------------------
+def test_depthwise_shapes_and_records(api, P):
+    dw = lambda tm, tn, tk, wm, wn, stages=1, vec=4, unroll=8, order=0: api.make_schedule(
+        wl.CLS_DWCONV_BIAS_RELU6, api.TT_SK_DWCONV, tm, tn, tk, wm, wn, 0, 1, order, vec, unroll, stages)
+    direct = api.make_schedule(wl.CLS_DWCONV_BIAS_RELU6, api.TT_SK_DIRECT, 1, 1, 1, 1, 1, 0, 1, 0, 1, 1, 1)
+    for n, c, hw, st in ((2, 32, 112, 1), (1, 96, 112, 2), (2, 144, 56, 2), (3, 192, 28, 1), (2, 576, 14, 2), (4, 960, 7, 1)):
+        k = wl.Kernel(wl.CLS_DWCONV_BIAS_RELU6, wl.ConvShape(n, c, hw, hw, c, 3, 3, st, st, 1, 1, wl.F32), 1, f"dw_{c}_{hw}_s{st}")
+        ho = k.shape.ho
+        scheds = [None, direct]
+        if ho >= 28:
+            scheds += [dw(4, 28, 4, 1, 4), dw(8, 16, 2, 2, 1, stages=2), dw(2, 28, 8, 2, 7, stages=2, order=3),
+                       dw(4, 8, 8, 4, 2, unroll=1)]
+        if ho >= 7:
+            scheds += [dw(7, 7, 16, 1, 1), dw(7, 7, 64, 7, 1, stages=2), dw(4, 4, 16, 2, 2)]
+        P.check_kernel(k, scheds)
+
+
+# ---- error behaviour --------------------------------------------------------------------------------
+def test_invalid_records_return_errors_and_write_nothing(api, P):
+    import torch
+    from paper_2201_05587_amd import harness
+    k = wl.resnet18_kernels()[13]  # 7x7 maps: M = 49
+    dk = harness.device_kernel(k, 5)
+    dk.output().fill_(7.0)
+    too_big = mfma(api, k.cls, 64, 64, 32, 32, 32, 32)
+    assert dk.run(too_big) == api.TT_ERR_INVALID_SCHEDULE
+    other = mfma(api, wl.CLS_CONV2D_ADD, 32, 32, 32, 16, 16, 16)
+    assert dk.run(other) == api.TT_ERR_CLASS_MISMATCH
+    malformed = mfma(api, k.cls, 32, 32, 32, 48, 16, 16)
+    assert dk.run(malformed) == api.TT_ERR_BAD_ARG
+    k2 = conv_kernel(k.cls, 1, 64, 14, 256, 3, 1)       # M = 196, N = 256
+    dk2 = harness.device_kernel(k2, 6)
+    dk2.output().fill_(7.0)
+    no_variant = mfma(api, k.cls, 128, 256, 32, 32, 64, 32)   # well-formed, applies, but is not compiled
+    assert api.tt_schedule_apply(no_variant, k2.cls, k2.shape).status == api.TT_OK
+    assert dk2.run(no_variant) == api.TT_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((dk2.output() == 7.0).all())
+    # split-K without enough workspace
+    dk.desc.ws_bytes = 16
+    assert dk.run(mfma(api, k.cls, 32, 32, 32, 16, 16, 16, split_k=4)) == api.TT_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert bool((dk.output() == 7.0).all())
+    # residual class without a residual tensor, misaligned pointer
+    x = dk.tensors["x"]
+    rc = api.lib.tt_conv2d_bias_relu(x.data_ptr() + 4, dk.desc.bufs[1], dk.desc.bufs[2], dk.desc.bufs[3], dk.desc.bufs[4],
+                                     __import__("ctypes").byref(dk.cshape), k.cls, None, None, 0, None)
+    assert rc == api.TT_ERR_BAD_ARG
+
+
+# ---- sweep ------------------------------------------------------------------------------------------
+def test_transfer_sweep_on_cfg1(api, P):
+    from paper_2201_05587_amd import harness
+    target, donor = wl.cfg1_target(), wl.cfg1_donor()
+    E = target.cls
+    pool = [mfma(api, E, 32, 32, 32, 16, 16, 16), mfma(api, E, 64, 64, 32, 32, 32, 32), mfma(api, E, 128, 64, 32, 64, 32, 32),
+            mfma(api, E, 128, 128, 32, 64, 64, 32),
+            mfma(api, wl.CLS_CONV2D_ADD, 32, 32, 32, 16, 16, 16),          # other class: never tried
+            mfma(api, E, 64, 64, 32, 32, 32, 32, split_k=32)]              # 18 K tiles: invalid
+    dks = [harness.device_kernel(target, 11), harness.device_kernel(donor, 12)]
+    rows, table, evals, wall = api.tt_transfer_sweep(dks, pool, api.make_opts(warmup=1, samples=5))
+    assert evals == 2 * (1 + 5)
+    for r, t in zip(rows, table):
+        assert t[4] == -2.0 and r["n_other_class"] == 1
+        valid = [v for i, v in enumerate(t) if i != 4 and v >= 0]
+        assert r["n_valid"] == len(valid) and r["n_invalid"] == 5 - len(valid)
+        assert r["best_us"] == min(valid + [r["default_us"]])
+        assert all(v > 0 for v in valid) and r["default_us"] > 0
+        if r["chosen"] >= 0:
+            assert t[r["chosen"]] == r["best_us"] < r["default_us"]
+    assert table[0][5] == -1.0          # split_k = 32 > 18 K tiles on the target
+    assert table[1][5] >= 0             # but fine on the donor (36 K tiles)
+    assert wall > 0
+    # the chosen record still computes the right thing
+    chosen = rows[0]["chosen"]
+    P.check_kernel(target, [pool[chosen] if chosen >= 0 else None], seed=11)
