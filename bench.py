@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the transfer-tuning hot path on one MI355X.
+
+A step is one network-shaped pass over the workload's fused kernels, each under the best
+TRANSFERRED schedule (the fastest valid donor record of its class, or the default as fallback),
+with all inputs resident in HBM.  `value` is the pass's algorithmic FLOPs over its time.  The same
+run re-times, per kernel, the record an exhaustive native sweep found and reports the transferred
+schedule's speed as a fraction of it.
+
+The sweeps themselves (native tuning of the donor kernels, the transfer sweep, the native sweep of
+the targets) are the search, not the step.  `--sweep` runs them here and stores their outcome next
+to the package (tuned/<workload>.json and .pool); without it the stored outcome is used, or, if
+there is none, the sweeps run first.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--sweep]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": 8000.0, "mfma_bf16": 2500.0, "mfma_f32": 157.3}  # GB/s, TFLOP/s (dense, published)
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--sweep", action="store_true", help="run the sweeps and store their outcome")
+    ap.add_argument("--retune-pool", action="store_true", help="also re-tune the donor kernels (the pool)")
+    ap.add_argument("--donor-limit", type=int, default=0, help="use only the first N donor kernels")
+    ap.add_argument("--level", type=int, default=1, help="size of the enumerated native space (0, 1, 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def knobs_to_record(api, knobs):
+    return None if knobs is None else api.make_schedule(**knobs)
+
+
+def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_path):
+    """Donor tuning (if needed), transfer sweep and native sweep of the targets; writes the tuned file."""
+    import torch
+    t_all = time.time()
+    if args.retune_pool or not os.path.exists(pool_path):
+        if args.donor_limit:
+            donors = donors[:args.donor_limit]
+        log(f"[pool] native-tuning {len(donors)} donor kernels")
+        t0 = time.time()
+        pool = tune.tune_donors(donors, cfg + 100, args.level, log)
+        tune.save_pool(pool_path, pool, [k.name for k in donors])
+        pool_seconds = time.time() - t0
+    else:
+        pool = tune.load_pool(pool_path)
+        pool_seconds = None
+    log(f"[sweep] transfer sweep: {len(dks)} kernels x {len(pool)} records")
+    rows, table, evals, wall = api.tt_transfer_sweep(dks, pool, api.make_opts(**tune.FULL))
+    out = dict(workload=args.workload, pool_records=len(pool), pool_seconds=pool_seconds, transfer_pairs=evals,
+               transfer_wall_seconds=wall, kernels=[])
+    n_invalid = sum(r["n_invalid"] for r in rows)
+    out["transfer_invalid_pairs"] = n_invalid
+    log(f"[sweep] {evals} pairs in {wall:.1f}s, {n_invalid} invalid")
+    spaces = {}
+    t0 = time.time()
+    for k, dk, r in zip(targets, dks, rows):
+        key = (k.cls, k.shape.dtype)
+        if key not in spaces:
+            spaces[key] = api.tt_schedule_space(k.cls, k.shape.dtype, args.level)
+        best, best_us, default_us, n_valid, n_rec = tune.native_sweep(dk, args.level, space=spaces[key])
+        chosen = pool[r["chosen"]] if r["chosen"] >= 0 else None
+        out["kernels"].append(dict(
+            name=k.name, cls=k.cls, chosen_pool_index=r["chosen"],
+            transfer=None if chosen is None else chosen.knobs(), transfer_us=r["best_us"], default_us=r["default_us"],
+            n_valid=r["n_valid"], n_invalid=r["n_invalid"],
+            native=None if best is None else best.knobs(), native_us=best_us, native_valid=n_valid, native_space=n_rec))
+        log(f"[native] {k.name:34s} transfer {r['best_us']:9.2f} us  native {best_us:9.2f} us  default "
+            f"{r['default_us']:9.2f} us  ratio {best_us / r['best_us']:.3f}  ({n_valid}/{n_rec} valid)")
+    out["native_wall_seconds"] = time.time() - t0
+    out["total_seconds"] = time.time() - t_all
+    tune.save_json(tuned_path, out)
+    torch.cuda.synchronize()
+    return out
+
+
+def cpu_baseline_leg(wl, targets, budget_s=20.0):
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from oracle import ops as O
+    import parity
+    import dataclasses
+    cores = O.max_threads()
+    flops = secs = 0.0
+    used = []
+    # one image (batch 1) of each layer, largest-work layers first, until the time budget is spent
+    order = sorted(range(len(targets)), key=lambda i: -targets[i].flops())
+    for i in order:
+        k = targets[i]
+        s = k.shape
+        small = dataclasses.replace(s, n=1) if k.is_conv() else dataclasses.replace(s, m=min(s.m, 64))
+        kk = wl.Kernel(k.cls, small, 1, k.name)
+        inp = wl.make_inputs(kk, 99 + i)
+        t0 = time.perf_counter()
+        parity.oracle_output(kk, inp)
+        dt = time.perf_counter() - t0
+        flops += kk.flops()
+        secs += dt
+        used.append(k.name)
+        if secs > budget_s:
+            break
+    return dict(value=flops / secs / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
+                sample=f"oracle (naive C loops, fp64 accumulate, OpenMP) on {len(used)} of {len(targets)} layers at "
+                       f"batch 1 (dense/bmm: 64 rows), {secs:.1f} s of CPU work")
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(kernel/schedule pairs are independent and would shard by target kernel, see DESIGN.md)")
+        sys.exit(2)
+    import torch
+    from paper_2201_05587_amd import api, harness, tune
+    from paper_2201_05587_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU; there is no CPU fallback"
+    torch.cuda.set_device(0)
+    cfg, targets, donors = tune.workload(args.workload)
+    tuned_dir = os.path.join(ROOT, "paper_2201_05587_amd", "tuned")
+    os.makedirs(tuned_dir, exist_ok=True)
+    tuned_path = os.path.join(tuned_dir, f"{args.workload}.json")
+    pool_path = os.path.join(tuned_dir, f"{args.workload}.pool")
+
+    dks = [harness.device_kernel(k, wl.seed_for(cfg, i), max_split=8) for i, k in enumerate(targets)]
+    if args.sweep or not os.path.exists(tuned_path):
+        tuned = run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_path)
+        swept_here = True
+    else:
+        with open(tuned_path) as f:
+            tuned = json.load(f)
+        swept_here = False
+    by_name = {e["name"]: e for e in tuned["kernels"]}
+    transfer = [knobs_to_record(api, by_name[k.name]["transfer"]) for k in targets]
+    native = [knobs_to_record(api, by_name[k.name]["native"]) for k in targets]
+
+    # ---- same-run comparison: best transferred record vs the native-swept optimum, per kernel ----
+    opts = api.make_opts(**tune.FULL)
+    per_kernel = []
+    for k, dk, tr, na in zip(targets, dks, transfer, native):
+        rc_t, t_us, _ = api.tt_time_pair(dk, tr, opts)
+        rc_n, n_us, _ = api.tt_time_pair(dk, na, opts)
+        rc_d, d_us, _ = api.tt_time_pair(dk, None, opts)
+        assert rc_t == api.TT_OK and rc_n == api.TT_OK and rc_d == api.TT_OK, (k.name, rc_t, rc_n, rc_d)
+        per_kernel.append(dict(name=k.name, transfer_us=t_us, native_us=n_us, default_us=d_us,
+                               frac_of_native=min(n_us, t_us) / t_us, tflops=k.flops() / t_us / 1e6,
+                               gbps=k.algorithmic_bytes() / t_us / 1e3))
+    fracs = [p["frac_of_native"] for p in per_kernel]
+
+    # ---- timed region: K network-shaped passes under the transferred schedules ----
+    klist = api.KernelList(dks, transfer)
+    pass_flops = sum(k.flops() * k.use_count for k in targets)
+    klist.run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    klist.run(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = pass_flops / (elapsed / args.steps) / 1e12
+
+    # ---- roofline of the dominant kernel: HIP events around each layer's launches, grouped by kernel symbol ----
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    groups = {}
+    reps = 20
+    for k, dk, tr in zip(targets, dks, transfer):
+        rec = tr if tr is not None else api.tt_schedule_default(k.cls, k.shape)
+        plan = api.tt_schedule_apply(rec, k.cls, k.shape)
+        trans_b = getattr(k.shape, "trans_b", 1)
+        fam = 0 if k.is_conv() else (1 if trans_b else 2)
+        name = api.variant_name(plan, k.shape.dtype, fam)
+        one = api.KernelList([dk], [tr])
+        saved, one.descs[0].use_count = one.descs[0].use_count, 1
+        one.run(3)
+        e0.record()
+        one.run(reps)
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        g = groups.setdefault(name, dict(us=0.0, flops=0.0, bytes=0.0, launches=0, dtype=k.shape.dtype, layers=[]))
+        g["us"] += us * k.use_count
+        g["flops"] += k.flops() * k.use_count
+        g["bytes"] += k.algorithmic_bytes() * k.use_count
+        g["launches"] += k.use_count
+        g["layers"].append(k.name)
+    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["us"])
+    ridge_peak = PEAK["mfma_bf16"] if dom["dtype"] == wl.BF16 else PEAK["mfma_f32"]
+    ai = dom["flops"] / dom["bytes"]
+    if ai >= ridge_peak * 1e12 / (PEAK["hbm"] * 1e9):
+        roof = dict(bound="mfma", achieved=dom["flops"] / dom["us"] / 1e6, peak=ridge_peak, unit="TFLOP/s")
+    else:
+        roof = dict(bound="hbm", achieved=dom["bytes"] / dom["us"] / 1e3, peak=PEAK["hbm"], unit="GB/s")
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof.update(kernel=dom_name, avg_launch_us=dom["us"] / dom["launches"], launches_per_step=dom["launches"],
+                layers=dom["layers"], arithmetic_intensity=ai)
+
+    out = {
+        "metric": "fused-op TFLOP/s of best transferred schedule; % of native-swept optimum",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if targets[0].shape.dtype == wl.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {len(targets)} fused kernels, {sum(k.use_count for k in targets)} "
+                               f"launches per pass, {pass_flops / 1e9:.1f} GFLOP per pass",
+                   "pool_records": tuned["pool_records"], "swept_in_this_run": swept_here},
+        "pct_of_native_optimum": {"mean": 100.0 * sum(fracs) / len(fracs), "min": 100.0 * min(fracs),
+                                  "kernels_at_or_above_80pct": sum(f >= 0.8 for f in fracs), "kernels": len(fracs)},
+        "sweep": {"pairs": tuned["transfer_pairs"], "wall_seconds": tuned["transfer_wall_seconds"],
+                  "invalid_pairs": tuned["transfer_invalid_pairs"], "native_wall_seconds": tuned["native_wall_seconds"]},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_leg(wl, targets)
+    report = os.path.join(ROOT, "gpurun_out", f"bench_{args.workload}_kernels.json")
+    if os.path.isdir(os.path.dirname(report)):
+        tune.save_json(report, dict(per_kernel=per_kernel, groups=groups))
+    for p in per_kernel:
+        log(f"{p['name']:34s} transfer {p['transfer_us']:9.2f} us  native {p['native_us']:9.2f}  default "
+            f"{p['default_us']:9.2f}  {p['tflops']:8.1f} TFLOP/s {p['gbps']:8.1f} GB/s  frac {p['frac_of_native']:.3f}")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

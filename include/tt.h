@@ -292,6 +292,15 @@ int tt_time_pair(const tt_kernel_desc *kernel, const tt_schedule *sched, const t
                  void *stream, double *median_us, double *min_us);
 
 /*
+ * Enqueue a list of kernels back to back on `stream`: kernel i runs use_count times under
+ * scheds[i] (NULL entry or NULL array = default schedule), and the whole list runs `repeat` times
+ * (a network-shaped pass under the schedules a sweep chose, Section 4.3).  Does not synchronise.
+ * Stops at the first error and returns it.
+ */
+int tt_run_kernels(const tt_kernel_desc *kernels, const tt_schedule *const *scheds, int nk, int repeat,
+                   void *stream);
+
+/*
  * Enumerate the schedule space of a class for a data type: every compiled
  * kernel variant crossed with the run-time knobs (split_k, order, stages, vec,
  * unroll).  Writes up to `cap` records to out (host) and returns the total

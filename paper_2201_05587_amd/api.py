@@ -87,7 +87,7 @@ class tt_sweep_row(Structure):
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
            "tt_debug_tile_map", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
-           "tt_transfer_sweep", "tt_time_pair", "tt_schedule_space", "tt_sweep_select")
+           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select")
 
 
 def _load():
@@ -118,6 +118,8 @@ def _load():
                                       POINTER(c_int64), POINTER(c_double)]
     lib.tt_time_pair.argtypes = [POINTER(tt_kernel_desc), POINTER(tt_schedule), POINTER(tt_sweep_opts), c_void_p,
                                  POINTER(c_double), POINTER(c_double)]
+    lib.tt_run_kernels.argtypes = [POINTER(tt_kernel_desc), POINTER(POINTER(tt_schedule)), ctypes.c_int, ctypes.c_int,
+                                   c_void_p]
     lib.tt_schedule_space.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(tt_schedule), ctypes.c_int]
     lib.tt_sweep_select.argtypes = [POINTER(c_int32), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
                                     POINTER(c_double), ctypes.c_int, POINTER(tt_sweep_row)]
@@ -379,3 +381,31 @@ def tt_transfer_sweep(kernels, pool, opts=None):
                      n_invalid=rows[i].n_invalid, n_other_class=rows[i].n_other_class, best_us=rows[i].best_us,
                      default_us=rows[i].default_us) for i in range(nk)]
     return out_rows, table, evals.value, wall.value
+
+
+class KernelList:
+    """Kernels and their chosen records marshalled once, for repeated network-shaped passes."""
+
+    def __init__(self, kernels, scheds):
+        self.kernels, self.scheds = list(kernels), [None if s is None else s.copy() for s in scheds]
+        n = len(self.kernels)
+        self.descs = (tt_kernel_desc * max(n, 1))()
+        for i, k in enumerate(self.kernels):
+            ctypes.memmove(byref(self.descs[i]), byref(k.desc), ctypes.sizeof(tt_kernel_desc))
+        self.ptrs = (POINTER(tt_schedule) * max(n, 1))()
+        for i, s in enumerate(self.scheds):
+            if s is not None:
+                self.ptrs[i] = ctypes.pointer(s)
+        self.n = n
+
+    def run(self, repeat=1):
+        _check(lib.tt_run_kernels(self.descs, self.ptrs, self.n, repeat, _stream()), "tt_run_kernels")
+
+
+def variant_name(plan: tt_plan, dtype: int, family: int) -> str:
+    """Readable name of the kernel a plan launches (matches the demangled symbol's template arguments)."""
+    if plan.sketch == TT_SK_MFMA:
+        return (f"contract_kernel<{dtype}, {family}, {plan.tile_m}, {plan.tile_n}, {plan.tile_k}, {plan.wave_m}, "
+                f"{plan.wave_n}, {plan.mfma}>")
+    return {TT_SK_GEMV: f"gemv_kernel<{dtype}>", TT_SK_DWCONV: f"dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}>",
+            TT_SK_DIRECT: "direct_kernel"}[plan.sketch]

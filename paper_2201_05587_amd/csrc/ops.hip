@@ -304,6 +304,21 @@ extern "C" int tt_time_pair(const tt_kernel_desc *kernel, const tt_schedule *sch
     return time_pair(*kernel, sched, resolve(opts), static_cast<hipStream_t>(stream), t, median_us, min_us);
 }
 
+extern "C" int tt_run_kernels(const tt_kernel_desc *kernels, const tt_schedule *const *scheds, int nk, int repeat,
+                              void *stream)
+{
+    if (nk < 0 || repeat < 0 || (nk && !kernels)) return TT_ERR_BAD_ARG;
+    for (int r = 0; r < repeat; ++r)
+        for (int k = 0; k < nk; ++k) {
+            if (!kernels[k].shape) return TT_ERR_BAD_ARG;
+            for (int u = 0; u < kernels[k].use_count; ++u) {
+                const int rc = launch_kernel_desc(kernels[k], scheds ? scheds[k] : nullptr, stream);
+                if (rc != TT_OK) return rc;
+            }
+        }
+    return TT_OK;
+}
+
 extern "C" int tt_transfer_sweep(const tt_kernel_desc *kernels, int nk, const tt_schedule *pool, int np,
                                  const tt_sweep_opts *opts, void *stream, tt_sweep_row *rows, double *pair_us,
                                  int64_t *evaluations, double *wall_seconds)

@@ -1,0 +1,135 @@
+"""Sweeps over schedule records: native (exhaustive) tuning of a kernel, donor pools, pool files.
+
+All timing and selection run inside the library (``tt_transfer_sweep``); this module only prepares
+the arguments, keeps the records with their provenance and reads / writes the pool file, the
+reusable artefact of transfer-tuning (the paper's "auto-schedules of pre-tuned models", Section 4.3).
+"""
+from __future__ import annotations
+
+import json
+import time
+from typing import Dict, List, Optional, Sequence
+
+from . import api, harness
+from . import workloads as wl
+
+POOL_MAGIC = "# tt-pool v1: cls sketch tile_m tile_n tile_k wave_m wave_n mfma split_k order vec unroll stages | donor shape | donor_us | donor name"
+
+# cheap protocol for walking a large space, full protocol (paper Section 5.1: median of 10) for the finalists
+EXPLORE = dict(warmup=1, samples=3, min_sample_us=60, max_launches=16)
+FULL = dict(warmup=3, samples=10, min_sample_us=200, max_launches=64)
+
+
+def shape_ints(shape) -> List[int]:
+    cs = api.to_c_shape(shape)
+    vals = [getattr(cs, f) for f, _ in cs._fields_]
+    return vals + [0] * (12 - len(vals))
+
+
+def native_sweep(dk: api.DeviceKernel, level: int = 1, finalists: int = 4, space: Optional[list] = None):
+    """Exhaustive sweep of the class's schedule space on the kernel's own shape.
+
+    Returns (best_record, best_us, default_us, n_valid, n_records).  The space is walked with the
+    cheap protocol, the `finalists` fastest records and the default are re-timed with the full one.
+    """
+    dtype = dk.cshape.dtype
+    if space is None:
+        space = api.tt_schedule_space(dk.cls, dtype, level)
+    rows, table, _, _ = api.tt_transfer_sweep([dk], space, api.make_opts(**EXPLORE))
+    times = table[0]
+    ranked = sorted((t, i) for i, t in enumerate(times) if t >= 0)
+    top = [space[i] for _, i in ranked[:finalists]]
+    n_valid = len(ranked)
+    if not top:
+        rc, med, _ = api.tt_time_pair(dk, None, api.make_opts(**FULL))
+        return None, med, med, 0, len(space)
+    rows, table, _, _ = api.tt_transfer_sweep([dk], top, api.make_opts(**FULL))
+    r = rows[0]
+    best = top[r["chosen"]].copy() if r["chosen"] >= 0 else None
+    return best, r["best_us"], r["default_us"], n_valid, len(space)
+
+
+def tune_donors(kernels: Sequence[wl.Kernel], seed_cfg: int, level: int = 1, log=None) -> List[api.tt_schedule]:
+    """Native-tune every donor kernel; each contributes its optimum as one pool record."""
+    import torch
+    pool: List[api.tt_schedule] = []
+    spaces: Dict[tuple, list] = {}
+    for i, k in enumerate(kernels):
+        key = (k.cls, k.shape.dtype)
+        if key not in spaces:
+            spaces[key] = api.tt_schedule_space(k.cls, k.shape.dtype, level)
+        dk = harness.device_kernel(k, wl.seed_for(seed_cfg, i), max_split=8)
+        t0 = time.time()
+        best, best_us, default_us, n_valid, n_rec = native_sweep(dk, level, space=spaces[key])
+        if best is None:
+            best = api.tt_schedule_default(k.cls, k.shape)
+        best.id = len(pool)
+        for j, v in enumerate(shape_ints(k.shape)):
+            best.donor_shape[j] = v
+        best.donor_us = best_us
+        pool.append(best)
+        if log:
+            log(f"donor {i:3d} {k.name:34s} best {best_us:9.2f} us (default {default_us:9.2f}) "
+                f"{n_valid}/{n_rec} valid, {time.time() - t0:.1f}s  {best}")
+        del dk
+        torch.cuda.empty_cache()
+    return pool
+
+
+def save_pool(path: str, pool: Sequence[api.tt_schedule], names: Optional[Sequence[str]] = None) -> None:
+    with open(path, "w") as f:
+        f.write(POOL_MAGIC + "\n")
+        for i, r in enumerate(pool):
+            knobs = " ".join(str(getattr(r, k)) for k in api.tt_schedule.KNOBS)
+            shape = " ".join(str(v) for v in r.donor_shape)
+            f.write(f"{knobs} | {shape} | {r.donor_us:.3f} | {names[i] if names else ''}\n")
+
+
+def load_pool(path: str) -> List[api.tt_schedule]:
+    pool = []
+    with open(path) as f:
+        head = f.readline()
+        if not head.startswith("# tt-pool v1"):
+            raise ValueError(f"{path}: not a tt-pool v1 file")
+        for ln in f:
+            ln = ln.strip()
+            if not ln or ln.startswith("#"):
+                continue
+            knobs, shape, us, _ = [p.strip() for p in ln.split("|")]
+            vals = [int(v) for v in knobs.split()]
+            r = api.make_schedule(*vals, id=len(pool))
+            for j, v in enumerate(int(x) for x in shape.split()):
+                r.donor_shape[j] = v
+            r.donor_us = float(us)
+            pool.append(r)
+    return pool
+
+
+# ---- workloads: target kernels and the donor kernels whose native optima form the pool -------------
+def workload(name: str):
+    """(cfg index, target kernels, donor kernels) of a named configuration."""
+    if name == "cfg1":
+        return 1, [wl.cfg1_target()], [wl.cfg1_donor()]
+    if name == "cfg2":
+        return 2, wl.resnet18_kernels(1, wl.F32), wl.resnet50_kernels(1, wl.F32)
+    if name == "cfg3":
+        donors = wl.bert_kernels(seq=256) + wl.bert_kernels(seq=128, hidden=512, heads=4, ffn=2048) + \
+            wl.bert_kernels(seq=256, hidden=512, heads=4, ffn=512)
+        return 3, wl.bert_kernels(seq=128), donors
+    if name == "cfg4":
+        return 4, wl.mobilenetv2_kernels(16, wl.F32), wl.mobilenetv2_kernels(1, wl.F32) + \
+            [k for k in wl.resnet50_kernels(1, wl.F32) if k.is_conv()][:8]
+    if name == "cfg5":
+        targets = wl.resnet50_kernels(32, wl.BF16, with_dense=False)
+        exclude = {(k.cls, k.shape) for k in targets}
+        donors = []
+        for i in range(10):
+            donors += wl.synthetic_network(i, 32, wl.BF16, 30, exclude)
+        return 5, targets, donors
+    raise ValueError(f"unknown workload {name}")
+
+
+def save_json(path: str, obj) -> None:
+    with open(path, "w") as f:
+        json.dump(obj, f, indent=1)
+        f.write("\n")
