@@ -88,6 +88,13 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
     out["native_wall_seconds"] = time.time() - t0
     out["total_seconds"] = time.time() - t_all
     tune.save_json(tuned_path, out)
+    # a second copy where a remote run's outputs are collected, so the outcome can be committed
+    mirror = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(mirror):
+        import shutil
+        os.makedirs(os.path.join(mirror, "tuned"), exist_ok=True)
+        for p in (tuned_path, pool_path):
+            shutil.copy(p, os.path.join(mirror, "tuned", os.path.basename(p)))
     torch.cuda.synchronize()
     return out
 

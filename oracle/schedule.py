@@ -211,6 +211,35 @@ def gemm_extents(cls: int, shape: dict):
     return (shape["batch"], shape["m"], shape["n"], shape["k"])
 
 
+def staged_tile_bytes(cls: int, shape: dict, rec: dict) -> int:
+    """LDS bytes of one pipeline stage (resource model of the matrix-core sketch).
+
+    Operands contiguous along K are staged row-major, each row padded by 16 bytes.
+    Operands contiguous along the output axis (NCHW activations; the [K][N] matrix
+    of a non-transposed batch matmul) are staged K-major; their rows are padded so
+    that the row length is 32 mod 64 elements for bf16, and by 8 (32-wide block)
+    or 4 (16-wide block) elements for fp32.
+    """
+    elem = 4 if shape["dtype"] == DT_F32 else 2
+    tm, tn, tk = rec["tile_m"], rec["tile_n"], rec["tile_k"]
+
+    def row_major(rows):
+        return rows * (tk + 16 // elem) * elem
+
+    def k_major(cols):
+        if shape["dtype"] == DT_BF16:
+            pad = (32 - cols % 64) % 64
+        else:
+            pad = 8 if rec["mfma"] == 32 else 4
+        return tk * (cols + pad) * elem
+
+    if cls in CONV_CLASSES:
+        return k_major(tm) + row_major(tn)
+    if shape["trans_b"]:
+        return row_major(tm) + row_major(tn)
+    return row_major(tm) + k_major(tn)
+
+
 def _blank_plan():
     return {f: 0 for f in PLAN_FIELDS}
 
@@ -358,8 +387,7 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_NOT_DIVISIBLE)
     k_iters = ceil_div(k_tiles, rec["split_k"])
     eff_split_k = ceil_div(k_tiles, k_iters)  # no empty split
-    padk = 16 // elem
-    lds = rec["stages"] * (tm + tn) * (tk + padk) * elem
+    lds = rec["stages"] * staged_tile_bytes(cls, shape, rec)
     if lds > LDS_BUDGET:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
     if cls in CONV_CLASSES:

@@ -115,204 +115,377 @@ template <> struct Mma<TT_F32, 16> {
 };
 
 // ---- global -> register loaders ---------------------------------------------------------------------------------
+//
+// All loaders follow one rule: a fetch only ISSUES loads.  Every load is unconditional (an
+// address that would fall outside the tensor is replaced by a safe one inside it) and lands in a
+// register nothing reads until the slice is written to LDS, so the loads of slice t+1 stay in
+// flight during the matrix work of slice t.  Zero padding, tails and edge repair are applied by
+// the store step, which recomputes (or has kept) which parts of each 16-byte item are real.
+// There is one straight-line code path per kernel: how the activations are fetched is a
+// template parameter, not a run-time branch.
 
-// Rows of a K-contiguous matrix [rows_total][ld]: each thread fetches 16-byte chunks along K.
+// Unconditional loads into registers (addresses need only element alignment).
+__device__ __forceinline__ void load16(u32x4 &dst, const void *p) { __builtin_memcpy(&dst, p, 16); }
+__device__ __forceinline__ void load4(u32x4 &v, int at, const void *p)
+{
+    uint32_t t;
+    __builtin_memcpy(&t, p, 4);
+    v[at] = t;
+}
+
+// Shift the 16-byte value by whole elements: positive = towards higher element indices; zero fill.
+template <int DT> __device__ __forceinline__ u32x4 shift_elems(const u32x4 &v, int elems)
+{
+    constexpr int EB = DT == TT_F32 ? 32 : 16;
+    unsigned __int128 x = ((unsigned __int128)v[3] << 96) | ((unsigned __int128)v[2] << 64) |
+                          ((unsigned __int128)v[1] << 32) | (unsigned __int128)v[0];
+    x = elems >= 0 ? (x << (EB * elems)) : (x >> (EB * -elems));
+    u32x4 r = {(uint32_t)x, (uint32_t)(x >> 32), (uint32_t)(x >> 64), (uint32_t)(x >> 96)};
+    return r;
+}
+__device__ __forceinline__ uint32_t shift32(uint32_t x, int bits) { return bits >= 0 ? x << bits : x >> -bits; }
+
+// Zero the elements of a 16-byte item at positions >= keep (0 <= keep; keep >= CH keeps all).
+template <int DT> __device__ __forceinline__ u32x4 keep_first(u32x4 v, int keep)
+{
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        if constexpr (DT == TT_F32) {
+            v[h] = h < keep ? v[h] : 0u;
+        } else {
+            const uint32_t lo = 2 * h < keep ? 0xffffu : 0u, hi = 2 * h + 1 < keep ? 0xffff0000u : 0u;
+            v[h] &= lo | hi;
+        }
+    }
+    return v;
+}
+
+// Rows of a K-contiguous matrix [rows_total][K], K >= CH: each thread fetches 16-byte chunks along
+// K.  A chunk that would run past the end of its row is read CH elements back from the row end
+// and shifted down afterwards, so the access never leaves the matrix.
 template <int DT, int ROWS, int TK, int THREADS> struct RowKLoader {
     using E = typename ElemOf<DT>::type;
     static constexpr int CH = ElemOf<DT>::CH, CPR = TK / CH, TOTAL = ROWS * CPR;
     static constexpr int NL = (TOTAL + THREADS - 1) / THREADS;
     static constexpr int ROWB = (TK + CH) * (int)sizeof(E);
-
-    static __device__ __forceinline__ void load(u32x4 (&regs)[NL], const E *base, int64_t ld, int row0, int rows_total,
-                                                int k0, int k_end, int ev, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int c = tid + i * THREADS;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (TOTAL % THREADS == 0 || c < TOTAL) {
-                const int r = c / CPR, kc = c % CPR;
-                const int gr = row0 + r, gk = k0 + kc * CH;
-                if (gr < rows_total && gk < k_end) {
-                    const E *p = base + (int64_t)gr * ld + gk;
-                    if (ev == CH && gk + CH <= k_end) {
-                        v = *reinterpret_cast<const u32x4 *>(p);
-                    } else if (ev * (int)sizeof(E) == 8) {
-#pragma unroll
-                        for (int h = 0; h < 2; ++h)
-                            if (gk + (h + 1) * (CH / 2) <= k_end) {
-                                const uint2 t = *reinterpret_cast<const uint2 *>(p + h * (CH / 2));
-                                v[2 * h] = t.x;
-                                v[2 * h + 1] = t.y;
-                            }
-                    } else if (ev * (int)sizeof(E) == 4) {
-#pragma unroll
-                        for (int h = 0; h < 4; ++h)
-                            if (gk + (h + 1) * (CH / 4) <= k_end)
-                                v[h] = *reinterpret_cast<const uint32_t *>(p + h * (CH / 4));
-                    } else {
-                        // element-wise (bf16 with odd K)
-#pragma unroll
-                        for (int j = 0; j < CH; ++j)
-                            if (gk + j < k_end) {
-                                if constexpr (DT == TT_F32)
-                                    v[j] = __float_as_uint(p[j]);
-                                else
-                                    v[j / 2] |= (uint32_t)p[j] << (16 * (j & 1));
-                            }
-                    }
-                }
-            }
-            regs[i] = v;
-        }
-    }
-
-    static __device__ __forceinline__ void store(const u32x4 (&regs)[NL], unsigned char *lds, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int c = tid + i * THREADS;
-            if (TOTAL % THREADS == 0 || c < TOTAL) {
-                const int r = c / CPR, kc = c % CPR;
-                *reinterpret_cast<u32x4 *>(lds + r * ROWB + kc * 16) = regs[i];
-            }
-        }
-    }
-};
-
-// Rows whose elements along K are NOT contiguous in memory: the implicit-GEMM view of NCHW
-// activations (K = (c, r, s)) and the [K][N] operand of a non-transposed batch matmul.  Lanes
-// take neighbouring rows (contiguous in memory), each thread assembles CH consecutive K of its row.
-template <int DT, int FAM, int ROWS, int TK, int THREADS> struct GatherLoader {
-    using E = typename ElemOf<DT>::type;
-    static constexpr int CH = ElemOf<DT>::CH, CPR = TK / CH, TOTAL = ROWS * CPR;
-    static constexpr int NL = (TOTAL + THREADS - 1) / THREADS;
-    static constexpr int NR = ROWS > THREADS ? ROWS / THREADS : 1; // distinct rows a thread serves
-    static constexpr int ROWB = (TK + CH) * (int)sizeof(E);
-
-    struct Row {
-        int64_t base; // element offset of the row's image (conv) / the row index itself (NN)
-        int ih0, iw0;
-        bool valid;
+    struct State {
+        u32x4 raw[NL];
     };
 
-    static __device__ __forceinline__ int row_of(int slot, int tid)
-    {
-        return ROWS > THREADS ? tid + slot * THREADS : tid % ROWS;
-    }
-
-    static __device__ __forceinline__ void init(Row (&rows)[NR], const ContractArgs &g, int row0, int tid)
+    static __device__ __forceinline__ void load(State &st, const E *base, int K, int row0, int rows_total, int k0,
+                                                int tid)
     {
 #pragma unroll
-        for (int s = 0; s < NR; ++s) {
-            const int gr = row0 + row_of(s, tid);
-            Row r;
-            if constexpr (FAM == FAM_CONV) {
-                r.valid = gr < g.M;
-                const int hw = g.Ho * g.Wo;
-                const int img = gr / hw, pix = gr - img * hw;
-                const int p = pix / g.Wo, q = pix - p * g.Wo;
-                r.ih0 = p * g.stride_h - g.pad_h;
-                r.iw0 = q * g.stride_w - g.pad_w;
-                r.base = (int64_t)img * g.C * g.H * g.W;
-            } else {
-                r.valid = gr < g.N;
-                r.base = gr;
-                r.ih0 = r.iw0 = 0;
-            }
-            rows[s] = r;
+        for (int i = 0; i < NL; ++i) {
+            int c = tid + i * THREADS;
+            if (TOTAL % THREADS != 0) c = min(c, TOTAL - 1);
+            const int r = c / CPR, kc = c % CPR;
+            const int gr = min(row0 + r, rows_total - 1);
+            const int gk = min(k0 + kc * CH, K - CH);
+            load16(st.raw[i], base + (int64_t)gr * K + gk);
         }
     }
 
-    static __device__ __forceinline__ void load(u32x4 (&regs)[NL], const Row (&rows)[NR], const E *base,
-                                                const ContractArgs &g, int k0, int k_end, int tid)
+    static __device__ __forceinline__ void store(const State &st, unsigned char *lds, int K, int row0, int rows_total,
+                                                 int k0, int k_end, int tid)
     {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int c = tid + i * THREADS;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (TOTAL % THREADS == 0 || c < TOTAL) {
-                const int slot = ROWS > THREADS ? i % NR : 0;
-                const int kc = ROWS > THREADS ? i / NR : tid / ROWS + i * (THREADS / ROWS);
-                const Row &r = rows[slot];
-                const int k = k0 + kc * CH;
-                if (r.valid && k < k_end) {
-                    if constexpr (FAM == FAM_CONV) {
-                        const int rs = g.R * g.S;
-                        int cin = k / rs;
-                        const int rem = k - cin * rs;
-                        int fr = rem / g.S, fs = rem - fr * g.S;
-#pragma unroll
-                        for (int j = 0; j < CH; ++j) {
-                            const int ih = r.ih0 + fr, iw = r.iw0 + fs;
-                            if (k + j < k_end && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
-                                const E e = base[r.base + ((int64_t)cin * g.H + ih) * g.W + iw];
-                                if constexpr (DT == TT_F32)
-                                    v[j] = __float_as_uint(e);
-                                else
-                                    v[j / 2] |= (uint32_t)e << (16 * (j & 1));
-                            }
-                            if (++fs == g.S) {
-                                fs = 0;
-                                if (++fr == g.R) {
-                                    fr = 0;
-                                    ++cin;
-                                }
-                            }
-                        }
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < CH; ++j)
-                            if (k + j < k_end) {
-                                const E e = base[(int64_t)(k + j) * g.N + r.base];
-                                if constexpr (DT == TT_F32)
-                                    v[j] = __float_as_uint(e);
-                                else
-                                    v[j / 2] |= (uint32_t)e << (16 * (j & 1));
-                            }
-                    }
-                }
-            }
-            regs[i] = v;
-        }
-    }
-
-    static __device__ __forceinline__ void store(const u32x4 (&regs)[NL], unsigned char *lds, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int c = tid + i * THREADS;
-            if (TOTAL % THREADS == 0 || c < TOTAL) {
-                const int slot = ROWS > THREADS ? i % NR : 0;
-                const int kc = ROWS > THREADS ? i / NR : tid / ROWS + i * (THREADS / ROWS);
-                *reinterpret_cast<u32x4 *>(lds + row_of(slot, tid) * ROWB + kc * 16) = regs[i];
-            }
+            if (TOTAL % THREADS != 0 && c >= TOTAL) continue;
+            const int r = c / CPR, kc = c % CPR;
+            const int gk = k0 + kc * CH;
+            const int back = gk - min(gk, K - CH); // how far the load was moved back
+            u32x4 v = st.raw[i];
+            if (back > 0 || gk + CH > k_end) v = keep_first<DT>(shift_elems<DT>(v, -back), k_end - gk);
+            if (row0 + r >= rows_total) v = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4 *>(lds + r * ROWB + kc * 16) = v;
         }
     }
 };
 
-template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF>
+// ---- K-major tiles: operands whose memory is contiguous along the OUTPUT axis, not along K -----------------------
+//
+// NCHW activations seen as the implicit-GEMM matrix (K = (c, r, s); consecutive output pixels of
+// a row are consecutive input pixels) and the [K][N] operand of a non-transposed batch matmul.
+// The tile is kept in LDS as T[k][x], x contiguous, so global vectors are copied as they are.
+// Matrix-core fragments (8 consecutive K per lane for bf16) come out of the transposing LDS read
+// of gfx950: within 16 lanes, lane i supplies the address of 4 consecutive x of K-row i/4 and
+// receives the 4 K-rows of column i.  fp32 fragments are four 4-byte reads.
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Padded row length (elements) of a K-major tile: keeps the fragment reads free of bank conflicts.
+template <int DT, int ROWS, int MF> struct KMajorRow {
+    static constexpr int PAD = DT == TT_BF16 ? (32 + 64 - ROWS % 64) % 64 : (MF == 32 ? 8 : 4);
+    static constexpr int LEN = ROWS + PAD;
+};
+
+// Implicit-GEMM activation tile, K-major.  An item is one K-row times G = 16 bytes of consecutive
+// output pixels, fetched as 16 / VB loads of VB bytes: the whole item when a row of output
+// pixels is a multiple of G and the stride is 1 (VB = 16), pairs of bf16 pixels when rows are
+// even (VB = 4), else single pixels (VB = element size).
+//
+// Address generation is kept off the critical path.  What depends only on the thread's pixels is
+// computed once per workgroup: the element offset of filter tap (0, 0), one bit per filter row
+// saying whether that row falls inside the image, and one 4-bit code per filter column saying
+// whether the sub-vector is inside the row, outside, or hangs over its left or right end (then
+// the load is moved back inside and the code is the element shift that repairs it).  What depends
+// only on K - (channel, filter row, filter column) - advances by add-and-carry, never by division.
+template <int DT, int TM, int TK, int THREADS, int LEN, int VB> struct ConvTileLoader {
+    using E = typename ElemOf<DT>::type;
+    static constexpr int ES = (int)sizeof(E);
+    static constexpr int G = ElemOf<DT>::CH;              // pixels per item
+    static constexpr int V = VB / ES;                      // pixels per load
+    static constexpr int NS = 16 / VB;                     // loads per item
+    static constexpr int MG = TM / G;                      // items per K-row
+    static constexpr int KSTEP = THREADS / MG;             // K-rows between a thread's items
+    static constexpr int NL = (TK + KSTEP - 1) / KSTEP;    // items per thread and slice
+    static_assert(MG >= 1 && MG <= THREADS, "tile_m does not fit the workgroup");
+    static_assert(VB == 16 || VB == 4 || VB == ES, "unsupported activation fetch width");
+
+    struct Mixed { // a K index as (channel, filter row, filter column)
+        int c, r, s;
+    };
+    struct State {
+        int32_t off[NS];     // per sub-vector: element offset of tap (0, 0) of its first pixel
+        uint32_t rows[NS];   // bit r: filter row r is inside the image
+        uint32_t cols[NS];   // nibble s: 0 = outside, else 8 + element shift to apply after the load
+        uint32_t raw[NL][VB == 2 ? 8 : 4];
+        uint32_t fix[NL];    // nibble j: the code sub-vector j was loaded with
+        Mixed kpos;          // decomposition of the first K-row this thread serves in the next slice
+        Mixed step_item, step_tile;
+    };
+
+    static __device__ __forceinline__ Mixed decompose(int k, int R, int S)
+    {
+        Mixed m;
+        m.c = k / (R * S);
+        const int rem = k - m.c * R * S;
+        m.r = rem / S;
+        m.s = rem - m.r * S;
+        return m;
+    }
+    static __device__ __forceinline__ Mixed advance(Mixed a, const Mixed &d, int R, int S)
+    {
+        a.s += d.s;
+        const int cs = a.s >= S;
+        a.s -= cs ? S : 0;
+        a.r += d.r + cs;
+        const int cr = a.r >= R;
+        a.r -= cr ? R : 0;
+        a.c += d.c + cr;
+        return a;
+    }
+
+    static __device__ __forceinline__ void init(State &st, const ContractArgs &g, int m0, int k_first, int tid)
+    {
+        const int mg = tid % MG;
+        const int hw = g.Ho * g.Wo;
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            st.off[j] = 0;
+            st.rows[j] = 0u;
+            st.cols[j] = 0u;
+            const int m = m0 + mg * G + j * V;
+            if (m >= g.M) continue;
+            const int img = m / hw, pix = m - img * hw;
+            const int p = pix / g.Wo, q = pix - p * g.Wo;
+            const int ih0 = p * g.stride_h - g.pad_h, iw0 = q * g.stride_w - g.pad_w;
+            st.off[j] = (img * g.C * g.H + ih0) * g.W + iw0;
+            uint32_t rows = 0u, cols = 0u;
+            for (int r = 0; r < g.R; ++r)
+                if (ih0 + r >= 0 && ih0 + r < g.H) rows |= 1u << r;
+            for (int s = 0; s < g.S; ++s) {
+                const int iw = iw0 + s;
+                if (iw > -V && iw < g.W) {
+                    const int shift = iw < 0 ? -iw : (iw + V > g.W ? g.W - V - iw : 0);
+                    cols |= (uint32_t)(shift + 8) << (4 * s);
+                }
+            }
+            st.rows[j] = rows;
+            st.cols[j] = cols;
+        }
+        st.kpos = decompose(k_first + tid / MG, g.R, g.S);
+        st.step_item = decompose(KSTEP, g.R, g.S);
+        st.step_tile = decompose(TK, g.R, g.S);
+    }
+
+    // Issue the loads of the slice whose first K index is k0 (slices must be fetched in order).
+    static __device__ __forceinline__ void load(State &st, const E *x, const ContractArgs &g, int k0, int k_end, int tid)
+    {
+        const int kl0 = tid / MG;
+        const int hw_in = g.H * g.W;
+        Mixed kp = st.kpos;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int kl = kl0 + i * KSTEP;
+            const uint32_t k_ok = (kl < TK) & (k0 + kl < k_end);
+            const int koff = kp.c * hw_in + kp.r * g.W + kp.s;
+            uint32_t fix = 0u;
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const uint32_t present = k_ok & (st.rows[j] >> kp.r) & 1u;
+                const uint32_t code = present ? (st.cols[j] >> (4 * kp.s)) & 15u : 0u;
+                // nothing to read: point at the start of the tensor, which is always readable
+                const int idx = code ? st.off[j] + koff + (int)code - 8 : 0;
+                fix |= code << (4 * j);
+                const E *p = x + idx;
+                if constexpr (VB == 16) {
+                    u32x4 t;
+                    load16(t, p);
+                    st.raw[i][0] = t[0];
+                    st.raw[i][1] = t[1];
+                    st.raw[i][2] = t[2];
+                    st.raw[i][3] = t[3];
+                } else if constexpr (VB == 4) {
+                    uint32_t t;
+                    __builtin_memcpy(&t, p, 4);
+                    st.raw[i][j] = t;
+                } else {
+                    st.raw[i][j] = *reinterpret_cast<const uint16_t *>(p);
+                }
+            }
+            st.fix[i] = fix;
+            kp = advance(kp, st.step_item, g.R, g.S);
+        }
+        st.kpos = advance(st.kpos, st.step_tile, g.R, g.S);
+    }
+
+    static __device__ __forceinline__ void store(const State &st, unsigned char *lds, int tid)
+    {
+        const int mg = tid % MG, kl0 = tid / MG;
+        constexpr int EB = 8 * ES;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int kl = kl0 + i * KSTEP;
+            if (KSTEP * NL > TK && kl >= TK) continue;
+            u32x4 v;
+            const uint32_t fix = st.fix[i];
+            if constexpr (VB == 16) {
+                const int code = (int)(fix & 15u);
+                v = shift_elems<DT>(u32x4{st.raw[i][0], st.raw[i][1], st.raw[i][2], st.raw[i][3]}, code - 8);
+                if (code == 0) v = u32x4{0u, 0u, 0u, 0u};
+            } else if constexpr (VB == 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int code = (int)((fix >> (4 * j)) & 15u);
+                    // fp32: a single element, present or not; bf16: a pair that may need a one-element shift
+                    if constexpr (DT == TT_F32)
+                        v[j] = code != 0 ? st.raw[i][j] : 0u;
+                    else
+                        v[j] = code != 0 ? shift32(st.raw[i][j], EB * (code - 8)) : 0u;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t lo = ((fix >> (8 * j)) & 15u) != 0u ? (st.raw[i][2 * j] & 0xffffu) : 0u;
+                    const uint32_t hi = ((fix >> (8 * j + 4)) & 15u) != 0u ? (st.raw[i][2 * j + 1] << 16) : 0u;
+                    v[j] = lo | hi;
+                }
+            }
+            *reinterpret_cast<u32x4 *>(lds + ((size_t)kl * LEN + mg * G) * sizeof(E)) = v;
+        }
+    }
+};
+
+// [K][N] operand of a non-transposed batch matmul (N >= G): rows of the matrix are rows of the
+// K-major tile.  A 16-byte item that would run past the end of its row is read G elements back
+// from the row end and shifted down afterwards.
+template <int DT, int TN, int TK, int THREADS, int LEN> struct KRowTileLoader {
+    using E = typename ElemOf<DT>::type;
+    static constexpr int G = ElemOf<DT>::CH, NG = TN / G;
+    static constexpr int KSTEP = THREADS / NG;
+    static constexpr int NL = (TK + KSTEP - 1) / KSTEP;
+    static_assert(NG >= 1 && NG <= THREADS, "tile_n does not fit the workgroup");
+    struct State {
+        u32x4 raw[NL];
+    };
+
+    static __device__ __forceinline__ void load(State &st, const E *b, int N, int K, int n0, int k0, int tid)
+    {
+        const int ng = tid % NG, kl0 = tid / NG;
+        const int n = min(n0 + ng * G, N - G);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int k = min(k0 + kl0 + i * KSTEP, K - 1);
+            load16(st.raw[i], b + (int64_t)k * N + n);
+        }
+    }
+
+    static __device__ __forceinline__ void store(const State &st, unsigned char *lds, int N, int n0, int k0, int k_end,
+                                                 int tid)
+    {
+        const int ng = tid % NG, kl0 = tid / NG;
+        const int n = n0 + ng * G;
+        const int back = n - min(n, N - G);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int kl = kl0 + i * KSTEP;
+            if (KSTEP * NL > TK && kl >= TK) continue;
+            u32x4 v = st.raw[i];
+            if (back > 0) v = keep_first<DT>(shift_elems<DT>(v, -back), N - n);
+            if (k0 + kl >= k_end || n >= N) v = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4 *>(lds + ((size_t)kl * LEN + ng * G) * sizeof(E)) = v;
+        }
+    }
+};
+
+// Fragment of a K-major tile for lane (column x = x_base + lane % MF, K group = lane / MF) at K offset kk.
+template <int DT, int MF, int LEN> __device__ __forceinline__ u32x4 kmajor_fragment(const unsigned char *tile, int x_base,
+                                                                                     int kk, int lane)
+{
+    if constexpr (DT == TT_BF16) {
+        const int i = lane & 15, xblk = (lane % MF) / 16, kg = lane / MF;
+        const int row = kk + kg * 8 + (i >> 2), col = x_base + xblk * 16 + 4 * (i & 3);
+        const unsigned char *p = tile + ((size_t)row * LEN + col) * 2;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + (size_t)4 * LEN * 2));
+        const uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
+        return u32x4{l.x, l.y, h.x, h.y};
+    } else {
+        const int x = x_base + lane % MF, kg = lane / MF;
+        const float *p = reinterpret_cast<const float *>(tile) + (size_t)(kk + kg * 4) * LEN + x;
+        return u32x4{__float_as_uint(p[0]), __float_as_uint(p[LEN]), __float_as_uint(p[2 * LEN]),
+                     __float_as_uint(p[3 * LEN])};
+    }
+}
+
+// LDS bytes of one pipeline stage: the A tile followed by the B tile.
+template <int DT, int FAM, int TM, int TN, int TK, int MF> struct StageLayout {
+    using E = typename ElemOf<DT>::type;
+    static constexpr int CH = ElemOf<DT>::CH, ES = (int)sizeof(E);
+    static constexpr int ROWB = (TK + CH) * ES; // row of a K-contiguous tile, padded by 16 bytes
+    static constexpr int LEN_A = KMajorRow<DT, TM, MF>::LEN, LEN_B = KMajorRow<DT, TN, MF>::LEN;
+    static constexpr int A_BYTES = FAM == FAM_CONV ? TK * LEN_A * ES : TM * ROWB;
+    static constexpr int B_BYTES = FAM == FAM_GEMM_NN ? TK * LEN_B * ES : TN * ROWB;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+};
+
+// AM = bytes per activation load of the conv family (16, 4 or the element size); 0 for the others.
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int AM>
 __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(const ContractArgs g)
 {
     using E = typename ElemOf<DT>::type;
+    using L = StageLayout<DT, FAM, TM, TN, TK, MF>;
     constexpr int CH = ElemOf<DT>::CH, ES = (int)sizeof(E);
     constexpr int THREADS = (TM / WM) * (TN / WN) * 64;
-    constexpr int ROWB = (TK + CH) * ES;
-    constexpr int A_BYTES = TM * ROWB, B_BYTES = TN * ROWB, STAGE_BYTES = A_BYTES + B_BYTES;
-    constexpr bool SWAP = FAM == FAM_CONV; // matrix-core rows = N side
+    constexpr int ROWB = L::ROWB, A_BYTES = L::A_BYTES, STAGE_BYTES = L::STAGE_BYTES;
+    constexpr bool SWAP = FAM == FAM_CONV; // matrix-core rows = N side, columns = M side
     constexpr int WR = SWAP ? WN : WM, WC = SWAP ? WM : WN;
     constexpr int NWR = SWAP ? TN / WN : TM / WM; // waves along the matrix-core row axis
     constexpr int NI = WR / MF, NJ = WC / MF;
     constexpr int LG = 64 / MF, KS = CH * LG, NKS = TK / KS;
     constexpr int ACC = MF * MF / 64;
+    constexpr bool C_KMAJOR = FAM != FAM_GEMM_TN;     // the column-side tile is K-major
+    constexpr int LEN_C = SWAP ? L::LEN_A : L::LEN_B; // its padded row length
     static_assert(TK % KS == 0, "tile_k must be a multiple of the K granule");
     using M = Mma<DT, MF>;
     using ALoad = RowKLoader<DT, TM, TK, THREADS>;
-    using AGather = GatherLoader<DT, FAM_CONV, TM, TK, THREADS>;
+    using AConv = ConvTileLoader<DT, TM, TK, THREADS, L::LEN_A, FAM == FAM_CONV ? AM : 16>;
     using BLoad = RowKLoader<DT, TN, TK, THREADS>;
-    using BGather = GatherLoader<DT, FAM_GEMM_NN, TN, TK, THREADS>;
-    constexpr int NLA = FAM == FAM_CONV ? AGather::NL : ALoad::NL;
-    constexpr int NLB = FAM == FAM_GEMM_NN ? BGather::NL : BLoad::NL;
+    using BKRow = KRowTileLoader<DT, TN, TK, THREADS, L::LEN_B>;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -329,33 +502,35 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
         b_base += (int64_t)bidx * g.N * g.K;
     }
 
-    typename AGather::Row a_rows[AGather::NR];
-    typename BGather::Row b_rows[BGather::NR];
-    if constexpr (FAM == FAM_CONV) AGather::init(a_rows, g, tc.m0, tid);
-    if constexpr (FAM == FAM_GEMM_NN) BGather::init(b_rows, g, tc.n0, tid);
+    // registers holding the slice in flight (only the members of the family in use are live)
+    typename AConv::State a_conv;
+    typename BKRow::State b_krow;
+    typename ALoad::State a_rows;
+    typename BLoad::State b_rows;
+    if constexpr (FAM == FAM_CONV) AConv::init(a_conv, g, tc.m0, tc.k0, tid);
 
-    u32x4 ra[NLA], rb[NLB];
     auto fetch = [&](int kt) {
         const int k0 = tc.k0 + kt * TK;
         if constexpr (FAM == FAM_CONV)
-            AGather::load(ra, a_rows, a_base, g, k0, k_end, tid);
+            AConv::load(a_conv, a_base, g, k0, k_end, tid);
         else
-            ALoad::load(ra, a_base, g.K, tc.m0, g.M, k0, k_end, g.eff_vec_a, tid);
+            ALoad::load(a_rows, a_base, g.K, tc.m0, g.M, k0, tid);
         if constexpr (FAM == FAM_GEMM_NN)
-            BGather::load(rb, b_rows, b_base, g, k0, k_end, tid);
+            BKRow::load(b_krow, b_base, g.N, g.K, tc.n0, k0, tid);
         else
-            BLoad::load(rb, b_base, g.K, tc.n0, g.N, k0, k_end, g.eff_vec_b, tid);
+            BLoad::load(b_rows, b_base, g.K, tc.n0, g.N, k0, tid);
     };
-    auto stash = [&](int stage) {
+    auto stash = [&](int stage, int kt) {
+        const int k0 = tc.k0 + kt * TK;
         unsigned char *sa = smem + stage * STAGE_BYTES, *sb = sa + A_BYTES;
         if constexpr (FAM == FAM_CONV)
-            AGather::store(ra, sa, tid);
+            AConv::store(a_conv, sa, tid);
         else
-            ALoad::store(ra, sa, tid);
+            ALoad::store(a_rows, sa, g.K, tc.m0, g.M, k0, k_end, tid);
         if constexpr (FAM == FAM_GEMM_NN)
-            BGather::store(rb, sb, tid);
+            BKRow::store(b_krow, sb, g.N, tc.n0, k0, k_end, tid);
         else
-            BLoad::store(rb, sb, tid);
+            BLoad::store(b_rows, sb, g.K, tc.n0, g.N, k0, k_end, tid);
     };
 
     typename M::Acc acc[NI][NJ];
@@ -377,8 +552,12 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
         for (int i = 0; i < NI; ++i)
             rf[i] = *reinterpret_cast<const u32x4 *>(sr + r_off + i * MF * ROWB + ks * KS * ES);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            cf[j] = *reinterpret_cast<const u32x4 *>(sc + c_off + j * MF * ROWB + ks * KS * ES);
+        for (int j = 0; j < NJ; ++j) {
+            if constexpr (C_KMAJOR)
+                cf[j] = kmajor_fragment<DT, MF, LEN_C>(sc, wc * WC + j * MF, ks * KS, lane);
+            else
+                cf[j] = *reinterpret_cast<const u32x4 *>(sc + c_off + j * MF * ROWB + ks * KS * ES);
+        }
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -386,7 +565,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     };
 
     fetch(0);
-    stash(0);
+    stash(0, 0);
     __syncthreads();
     int cur = 0;
     const bool two_stage = g.stages == 2;
@@ -405,7 +584,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
         }
         if (more) {
             if (!two_stage) __syncthreads();
-            stash(two_stage ? cur ^ 1 : 0);
+            stash(two_stage ? cur ^ 1 : 0, it + 1);
         }
         __syncthreads();
         if (two_stage) cur ^= 1;
@@ -468,10 +647,10 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     }
 }
 
-template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF>
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int AM>
 int launch_contract(const ContractArgs &args, int grid, int lds_bytes, void *stream)
 {
-    auto kern = contract_kernel<DT, FAM, TM, TN, TK, WM, WN, MF>;
+    auto kern = contract_kernel<DT, FAM, TM, TN, TK, WM, WN, MF, AM>;
     static int raised = 0; // largest dynamic-LDS size this kernel has been enabled for
     if (lds_bytes > 48 * 1024 && lds_bytes > raised) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

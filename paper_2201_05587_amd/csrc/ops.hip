@@ -92,6 +92,11 @@ extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bia
     tt_plan plan;
     const int rc = make_plan(sched, cls, shape, ws, ws_bytes, &plan);
     if (rc != TT_OK) return rc;
+    // the matrix-core kernel addresses activations with 32-bit element offsets and keeps one bit per
+    // filter row and four per filter column
+    if (plan.sketch == TT_SK_MFMA &&
+        ((int64_t)shape->n * shape->c * shape->h * shape->w >= (1ll << 31) || shape->r > 32 || shape->s > 8))
+        return TT_ERR_UNSUPPORTED;
     ContractArgs g;
     std::memset(&g, 0, sizeof g);
     fill_common(g, plan, sched, cls, shape->dtype);
@@ -114,6 +119,14 @@ extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bia
     g.pad_w = shape->pad_w;
     g.Ho = conv_out(shape->h, shape->r, shape->stride_h, shape->pad_h);
     g.Wo = conv_out(shape->w, shape->s, shape->stride_w, shape->pad_w);
+    if (shape->r == 1 && shape->s == 1 && shape->pad_h == 0 && shape->pad_w == 0 && shape->stride_h == 1 &&
+        shape->stride_w == 1) {
+        // unit-stride pointwise conv: every (h, w) plane is one long row, so vectors may span image rows
+        g.W = shape->h * shape->w;
+        g.H = 1;
+        g.Wo = g.W;
+        g.Ho = 1;
+    }
     return run_contraction(g, plan, FAM_CONV, stream);
 }
 

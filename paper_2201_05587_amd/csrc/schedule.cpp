@@ -145,12 +145,12 @@ int family_of(int cls, int trans_b)
     return FAM_GEMM_TN;
 }
 
-int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf)
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode)
 {
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         if (v.dtype == dtype && v.family == family && v.tile_m == tm && v.tile_n == tn && v.tile_k == tk &&
-            v.wave_m == wm && v.wave_n == wn && v.mfma == mf)
+            v.wave_m == wm && v.wave_n == wn && v.mfma == mf && v.amode == amode)
             return i;
     }
     return -1;
@@ -325,9 +325,20 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     if (strict && p.k_tiles % r.split_k) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_NOT_DIVISIBLE);
     p.k_iters = cdiv(p.k_tiles, r.split_k);
     p.eff_split_k = cdiv(p.k_tiles, p.k_iters);
-    const int64_t lds = (int64_t)r.stages * (r.tile_m + r.tile_n) * (r.tile_k + 16 / elem) * elem;
-    if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
     int trans_b = 1;
+    if (!is_conv_class(cls)) trans_b = static_cast<const tt_gemm_shape *>(shape)->trans_b;
+    // Staged tiles.  An operand that is contiguous along K is kept row-major with 16 bytes of row
+    // padding; one that is contiguous along the output axis (NCHW activations, the [K][N] matrix)
+    // is kept K-major with a row padding that depends on the data type and the matrix-core block.
+    auto rowk_bytes = [&](int rows) { return (int64_t)rows * (r.tile_k + 16 / elem) * elem; };
+    auto kmajor_bytes = [&](int cols) {
+        const int pad = dt == TT_BF16 ? (32 + 64 - cols % 64) % 64 : (r.mfma == 32 ? 8 : 4);
+        return (int64_t)r.tile_k * (cols + pad) * elem;
+    };
+    const int64_t a_bytes = is_conv_class(cls) ? kmajor_bytes(r.tile_m) : rowk_bytes(r.tile_m);
+    const int64_t b_bytes = (!is_conv_class(cls) && !trans_b) ? kmajor_bytes(r.tile_n) : rowk_bytes(r.tile_n);
+    const int64_t lds = (int64_t)r.stages * (a_bytes + b_bytes);
+    if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
     if (is_conv_class(cls)) {
         const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
         const int ho = conv_out(s->h, s->r, s->stride_h, s->pad_h), wo = conv_out(s->w, s->s, s->stride_w, s->pad_w);
@@ -338,7 +349,6 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         p.eff_vec_b = widest_dividing(vmax, e.K);
         p.eff_vec_c = widest_dividing(vmax, (int64_t)ho * wo);
     } else {
-        trans_b = static_cast<const tt_gemm_shape *>(shape)->trans_b;
         p.eff_vec_a = widest_dividing(vmax, e.K);
         p.eff_vec_b = trans_b ? widest_dividing(vmax, e.K) : widest_dividing(vmax, e.N);
         p.eff_vec_c = widest_dividing(vmax, e.N);
@@ -351,7 +361,19 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     p.block = 64 * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
     p.lds_bytes = (int)lds;
     p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
-    p.variant_id = find_variant(dt, family_of(cls, trans_b), r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma);
+    // How the conv kernels fetch activations: whole 16-byte items when the effective vector width
+    // covers one, pairs of bf16 pixels when rows are even, else single pixels.
+    int amode = 0;
+    if (is_conv_class(cls)) {
+        const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
+        const bool pointwise = s->r == 1 && s->s == 1 && s->pad_h == 0 && s->pad_w == 0 && s->stride_h == 1 &&
+                               s->stride_w == 1;
+        const int64_t row = pointwise ? (int64_t)s->h * s->w : s->w;
+        const int v = (p.eff_vec_a > row || (!pointwise && s->stride_w != 1)) ? 1 : p.eff_vec_a;
+        amode = v * elem >= 16 ? 16 : (dt == TT_BF16 && v >= 2 ? 4 : elem);
+    }
+    p.variant_id =
+        find_variant(dt, family_of(cls, trans_b), r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode);
     *plan = p;
     return TT_OK;
 }
@@ -437,6 +459,7 @@ extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out
             if (!fam_ok) continue;
             // batch matmul records do not carry the layout: list each tile once (TN and NN tables are the same)
             if (cls == TT_BATCH_MATMUL && v.family == FAM_GEMM_NN) continue;
+            if (v.family == FAM_CONV && v.amode != 16) continue; // one record per tile, whatever the fetch mode
             static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 32};
             const int n_split = level >= 1 ? 9 : 1;
             const int n_order = level >= 2 ? 6 : (level >= 1 ? 2 : 1);

@@ -138,13 +138,14 @@ struct DwArgs {
 
 struct Variant {
     int32_t dtype, family, tile_m, tile_n, tile_k, wave_m, wave_n, mfma;
+    int32_t amode; // conv family: bytes per activation load (16, 4 or the element size); 0 otherwise
     int (*launch)(const ContractArgs &args, int grid, int lds_bytes, void *stream);
 };
 
 // variant table (generated) and lookups
 extern const Variant kVariants[];
 extern const int kNumVariants;
-int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf);
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode);
 int family_of(int cls, int trans_b);
 
 // launchers of the non-matrix-core kernels (simple_kernels.hip)

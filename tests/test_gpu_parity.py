@@ -95,6 +95,37 @@ def test_conv_bf16(api, P):
         P.check_kernel(k, scheds)
 
 
+@pytest.mark.parametrize("dt", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("dims", [
+    (2, 16, 56, 32, 3, 1),    # rows of 56: full 16-byte vectors, one-element edge fix-ups
+    (3, 24, 14, 48, 3, 1),    # rows of 14: 2-element sub-vectors
+    (2, 8, 16, 32, 5, 1),     # 5x5, pad 2: edge shifts of up to two elements
+    (1, 4, 24, 16, 7, 1),     # 7x7, pad 3: edge shifts of up to three elements
+    (2, 32, 12, 32, 3, 1),    # rows of 12: 4-element sub-vectors
+    (5, 40, 7, 64, 3, 1),     # odd rows: element mode
+    (2, 48, 20, 96, 1, 1),    # pointwise: vectors span image rows (plane of 400 pixels)
+    (3, 36, 9, 64, 1, 1),     # pointwise with an odd plane (81 pixels): element mode across images
+])
+def test_conv_vector_gather_modes(api, P, dims, dt):
+    n, c, hw, kk, f, st = dims
+    cls = wl.CLS_CONV2D_BIAS_RELU
+    k = conv_kernel(cls, n, c, hw, kk, f, st, dtype=dt)
+    tk = 16 if dt == wl.F32 else 32
+    scheds = [None, mfma(api, cls, 32, 32, tk, 16, 16, 16), mfma(api, cls, 64, 32, tk * 2, 32, 32, 32, split_k=2, stages=1),
+              mfma(api, cls, 128, 32, tk, 32, 32, 32, order=1), mfma(api, cls, 16, 16, tk, 16, 16, 16, vec=2),
+              mfma(api, cls, 256, 32, tk, 64, 32, 16, vec=1)]
+    P.check_kernel(k, scheds, seed=77)
+
+
+def test_conv_padding_wider_than_filter_centre(api, P):
+    # pad larger than (filter - 1) / 2 makes the output wider than the input: vectors must not read outside a row
+    for dt in (wl.F32, wl.BF16):
+        k = conv_kernel(wl.CLS_CONV2D_ADD, 2, 8, 6, 16, 3, 1, dtype=dt, pad=2)   # 6x6 -> 8x8
+        assert k.shape.wo == 8
+        tk = 16 if dt == wl.F32 else 32
+        P.check_kernel(k, [None, mfma(api, k.cls, 32, 16, tk, 16, 16, 16), mfma(api, k.cls, 64, 16, tk, 16, 16, 16)])
+
+
 # ---- dense / batch matmul -------------------------------------------------------------------------
 def test_dense_classes(api, P):
     for cls in (wl.CLS_DENSE_ADD, wl.CLS_DENSE_BIAS_RELU, wl.CLS_DENSE_BIAS_GELU):
