@@ -309,6 +309,14 @@ int tt_run_kernels(const tt_kernel_desc *kernels, const tt_schedule *const *sche
  */
 int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out, int cap);
 
+/*
+ * Template arguments of a compiled matrix-core kernel variant (tt_plan.variant_id): out[9] =
+ * {dtype, family (0 conv, 1 GEMM with [N][K] B, 2 GEMM with [K][N] B), tile_m, tile_n, tile_k, wave_m,
+ * wave_n, mfma, bytes per activation load (conv family; 0 otherwise)} - the order they appear in the
+ * kernel's symbol name.  TT_ERR_BAD_ARG for an id outside the table.
+ */
+int tt_variant_info(int variant_id, int32_t out[9]);
+
 /* Pure selection step of the sweep on given times (host only; the rule tt_transfer_sweep uses). */
 int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t *pool_cls, int np, const double *pair_us,
                     const double *default_us, int allow_slower_than_default, tt_sweep_row *rows);

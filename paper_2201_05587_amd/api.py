@@ -87,7 +87,7 @@ class tt_sweep_row(Structure):
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
            "tt_debug_tile_map", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
-           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select")
+           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info")
 
 
 def _load():
@@ -121,6 +121,7 @@ def _load():
     lib.tt_run_kernels.argtypes = [POINTER(tt_kernel_desc), POINTER(POINTER(tt_schedule)), ctypes.c_int, ctypes.c_int,
                                    c_void_p]
     lib.tt_schedule_space.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(tt_schedule), ctypes.c_int]
+    lib.tt_variant_info.argtypes = [ctypes.c_int, POINTER(c_int32 * 9)]
     lib.tt_sweep_select.argtypes = [POINTER(c_int32), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
                                     POINTER(c_double), ctypes.c_int, POINTER(tt_sweep_row)]
     for name in EXPORTS:
@@ -402,10 +403,11 @@ class KernelList:
         _check(lib.tt_run_kernels(self.descs, self.ptrs, self.n, repeat, _stream()), "tt_run_kernels")
 
 
-def variant_name(plan: tt_plan, dtype: int, family: int) -> str:
-    """Readable name of the kernel a plan launches (matches the demangled symbol's template arguments)."""
+def variant_name(plan: tt_plan) -> str:
+    """Name of the kernel a plan launches, spelled like the demangled symbol rocprofv3 reports."""
     if plan.sketch == TT_SK_MFMA:
-        return (f"contract_kernel<{dtype}, {family}, {plan.tile_m}, {plan.tile_n}, {plan.tile_k}, {plan.wave_m}, "
-                f"{plan.wave_n}, {plan.mfma}>")
-    return {TT_SK_GEMV: f"gemv_kernel<{dtype}>", TT_SK_DWCONV: f"dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}>",
-            TT_SK_DIRECT: "direct_kernel"}[plan.sketch]
+        info = (c_int32 * 9)()
+        _check(lib.tt_variant_info(plan.variant_id, byref(info)), "tt_variant_info")
+        return "tt::contract_kernel<" + ", ".join(str(v) for v in info) + ">"
+    return {TT_SK_GEMV: "tt::gemv_kernel", TT_SK_DWCONV: f"tt::dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}>",
+            TT_SK_DIRECT: "tt::direct_kernel"}[plan.sketch]

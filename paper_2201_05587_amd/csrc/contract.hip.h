@@ -590,57 +590,112 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
         if (two_stage) cur ^= 1;
     }
 
-    // ---- epilogue: bias, residual, activation, down-convert, store (or raw partial sums for split-K) ----
-    const bool partial = g.map.eff_split_k > 1;
-    const int64_t mn = (int64_t)g.M * g.N;
-    float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
-    const int hw = g.Ho * g.Wo;
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        const int col = wc * WC + j * MF + lane_r;
-        int64_t col_base; // output offset contributed by the contiguous-axis coordinate
-        bool col_ok;
-        int n_of_col = 0;
-        if constexpr (SWAP) {
-            const int m = tc.m0 + col;
-            col_ok = m < g.M;
-            const int img = m / hw, pix = m - img * hw;
-            col_base = (int64_t)img * g.N * hw + pix;
-        } else {
-            n_of_col = tc.n0 + col;
-            col_ok = n_of_col < g.N;
-            col_base = (int64_t)bidx * mn + n_of_col;
-        }
-        float bias_c = 0.0f;
-        if constexpr (!SWAP)
-            if (g.has_bias && col_ok && !partial) bias_c = load_as_float<DT>(g.bias, n_of_col);
+    // ---- epilogue ------------------------------------------------------------------------------------------
+    // The accumulators hold, per lane, 4 consecutive ROWS of one column, while memory is contiguous
+    // along COLUMNS.  Each wave therefore passes its tile through a private LDS region, one band of
+    // MF rows at a time, and reads it back so that a lane owns 8 consecutive columns of one row:
+    // bias, residual, activation and down-conversion then work on 16-byte vectors (or on the widest
+    // sub-vectors the output's row length allows), and stores are fully coalesced.  With split-K
+    // the raw partial sums go to the workspace in the same pattern.
+    {
+        constexpr int ESTRIDE = WC + (MF == 32 ? 8 : 4);      // floats per staged row (bank-conflict padding)
+        constexpr int CG = WC / 8;                            // 8-column groups per row
+        constexpr int ROWS_PER_PASS = 64 / CG;                // rows the 64 lanes cover at once
+        constexpr int PASSES = (MF + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
+        float *stage = reinterpret_cast<float *>(smem) + wave * (MF * ESTRIDE);
+        const bool partial = g.map.eff_split_k > 1;
+        const int64_t mn = (int64_t)g.M * g.N;
+        float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
+        const int hw = g.Ho * g.Wo;
+        int vc = g.eff_vec_c; // consecutive outputs that are contiguous in memory and all inside or all outside
+        const int cg = lane % CG, row_in_pass = lane / CG;
+        const int c0 = wc * WC + cg * 8; // first of this lane's 8 columns inside the workgroup tile
+
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
+            __syncthreads(); // the band before this one has been read (and the K loop is over)
 #pragma unroll
-            for (int v = 0; v < ACC; ++v) {
-                const int row_l = MF == 32 ? (v / 4) * 8 + lane_g * 4 + (v % 4) : lane_g * 4 + v;
-                const int row = wr * WR + i * MF + row_l;
-                int64_t idx;
-                bool ok = col_ok;
-                float bias_v = bias_c;
-                if constexpr (SWAP) {
-                    const int n = tc.n0 + row;
-                    ok = ok && n < g.N;
-                    idx = col_base + (int64_t)n * hw;
-                    if (g.has_bias && ok && !partial) bias_v = load_as_float<DT>(g.bias, n);
-                } else {
-                    const int m = tc.m0 + row;
-                    ok = ok && m < g.M;
-                    idx = col_base + (int64_t)m * g.N;
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int v = 0; v < ACC; ++v) {
+                    const int row_l = MF == 32 ? (v / 4) * 8 + lane_g * 4 + (v % 4) : lane_g * 4 + v;
+                    stage[row_l * ESTRIDE + j * MF + lane_r] = acc[i][j][v];
                 }
-                if (!ok) continue;
-                float val = acc[i][j][v];
-                if (partial) {
-                    ws[idx] = val;
-                } else {
-                    val += bias_v;
-                    if (g.has_res) val += load_as_float<DT>(g.res, idx);
-                    store_from_float<DT>(g.out, idx, apply_act(val, g.act));
+            __syncthreads();
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int row_l = ps * ROWS_PER_PASS + row_in_pass;
+                if (ROWS_PER_PASS * PASSES > MF && row_l >= MF) continue;
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
+                float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                const int row = wr * WR + i * MF + row_l;
+                // coordinates: SWAP (conv): row -> output channel n, columns -> pixels m; else row -> m, columns -> n
+                const int fixed = (SWAP ? tc.n0 : tc.m0) + row;
+                if (fixed >= (SWAP ? g.N : g.M)) continue;
+                const int first = (SWAP ? tc.m0 : tc.n0) + c0;
+                const int limit = SWAP ? g.M : g.N;
+                const float bias_row = (SWAP && g.has_bias && !partial) ? load_as_float<DT>(g.bias, fixed) : 0.0f;
+                // groups of vc consecutive columns
+                for (int e0 = 0; e0 < 8; e0 += vc) {
+                    const int colg = first + e0;
+                    if (colg >= limit) break;
+                    int64_t idx;
+                    if constexpr (SWAP) {
+                        const int img = colg / hw, pix = colg - img * hw;
+                        idx = ((int64_t)img * g.N + fixed) * hw + pix;
+                    } else {
+                        idx = (int64_t)bidx * mn + (int64_t)fixed * g.N + colg;
+                    }
+                    if (partial) {
+                        if (vc == 8) {
+                            *reinterpret_cast<f32x4 *>(ws + idx) = lo;
+                            *reinterpret_cast<f32x4 *>(ws + idx + 4) = hi;
+                        } else if (vc == 4) {
+                            *reinterpret_cast<f32x4 *>(ws + idx) = e0 == 0 ? lo : hi;
+                        } else {
+                            for (int e = 0; e < vc; ++e) ws[idx + e] = val[e0 + e];
+                        }
+                        continue;
+                    }
+                    if (vc == 8 && DT == TT_BF16) {
+                        u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
+                        if (g.has_res) resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
+                        if (!SWAP && g.has_bias)
+                            biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + colg);
+                        u32x4 outv;
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            float a = val[2 * h] + bias_row + __uint_as_float(biasv[h] << 16) +
+                                      __uint_as_float(resv[h] << 16);
+                            float b = val[2 * h + 1] + bias_row + __uint_as_float(biasv[h] & 0xffff0000u) +
+                                      __uint_as_float(resv[h] & 0xffff0000u);
+                            outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
+                                      ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
+                        }
+                        *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
+                    } else if (vc >= 4 && DT == TT_F32) {
+#pragma unroll
+                        for (int q4 = 0; q4 < 2; ++q4) {
+                            if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
+                            f32x4 r = q4 == 0 ? lo : hi;
+                            const int64_t at = idx + (q4 * 4 - e0);
+                            f32x4 add = {bias_row, bias_row, bias_row, bias_row};
+                            if (!SWAP && g.has_bias)
+                                add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + colg + (q4 * 4 - e0));
+                            if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
+                            *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
+                        }
+                    } else {
+                        for (int e = 0; e < vc; ++e) {
+                            float a = val[e0 + e] + bias_row;
+                            if (!SWAP && g.has_bias) a += load_as_float<DT>(g.bias, colg + e);
+                            if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
+                            store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
+                        }
+                    }
                 }
             }
         }
@@ -651,6 +706,10 @@ template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int A
 int launch_contract(const ContractArgs &args, int grid, int lds_bytes, void *stream)
 {
     auto kern = contract_kernel<DT, FAM, TM, TN, TK, WM, WN, MF, AM>;
+    // the epilogue stages one band of MF rows per wave in the same LDS
+    constexpr int WC_ = FAM == FAM_CONV ? WM : WN;
+    constexpr int EPI_BYTES = (TM / WM) * (TN / WN) * MF * (WC_ + (MF == 32 ? 8 : 4)) * 4;
+    if (lds_bytes < EPI_BYTES) lds_bytes = EPI_BYTES;
     static int raised = 0; // largest dynamic-LDS size this kernel has been enabled for
     if (lds_bytes > 48 * 1024 && lds_bytes > raised) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -394,6 +394,15 @@ extern "C" int tt_plan_tile(const tt_plan *plan, int64_t wg, int32_t out[8])
     return TT_OK;
 }
 
+extern "C" int tt_variant_info(int variant_id, int32_t out[9])
+{
+    if (!out || variant_id < 0 || variant_id >= kNumVariants) return TT_ERR_BAD_ARG;
+    const Variant &v = kVariants[variant_id];
+    const int32_t vals[9] = {v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode};
+    std::copy(vals, vals + 9, out);
+    return TT_OK;
+}
+
 extern "C" int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t *pool_cls, int np,
                                const double *pair_us, const double *default_us, int allow_slower, tt_sweep_row *rows)
 {
