@@ -43,6 +43,9 @@ def _load():
         i = ctypes.c_int
         lib.tt_oracle_conv2d.argtypes = [fp, fp, fp, fp, fp] + [i] * 13
         lib.tt_oracle_conv2d.restype = None
+        lib.tt_oracle_conv2d_points.argtypes = [fp, fp, fp, fp, ctypes.POINTER(ctypes.c_int), fp, ctypes.c_longlong] + \
+            [i] * 12
+        lib.tt_oracle_conv2d_points.restype = None
         lib.tt_oracle_dense.argtypes = [fp, fp, fp, fp] + [i] * 5
         lib.tt_oracle_dense.restype = None
         lib.tt_oracle_batch_matmul.argtypes = [fp, fp, fp] + [i] * 6
@@ -106,6 +109,31 @@ def conv2d(x, w, bias=None, res=None, stride=(1, 1), pad=(0, 0), act=ACT_NONE, a
     lib.tt_oracle_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(res), _ptr(y), n, c, h, wd, k, r, s,
                          stride[0], stride[1], pad[0], pad[1], act, int(acc64))
     return y
+
+
+def conv2d_points(x, w, coords, bias=None, res=None, stride=(1, 1), pad=(0, 0), act=ACT_NONE):
+    """conv2d (+bias) (+residual) (+activation) at the output coordinates coords[:, (n, k, p, q)] only."""
+    lib = _load()
+    x = _f32(x)
+    w = _f32(w)
+    n, c, h, wd = x.shape
+    k, c2, r, s = w.shape
+    if c2 != c:
+        raise ValueError("channel mismatch")
+    coords = np.ascontiguousarray(coords, dtype=np.int32)
+    if coords.ndim != 2 or coords.shape[1] != 4:
+        raise ValueError("coords must be [npts, 4]")
+    ho = conv_out_extent(h, r, stride[0], pad[0])
+    wo = conv_out_extent(wd, s, stride[1], pad[1])
+    if coords.size and (coords.min() < 0 or (coords.max(axis=0) >= np.array([n, k, ho, wo])).any()):
+        raise ValueError("coordinate out of range")
+    bias = None if bias is None else _f32(bias, (k,))
+    res = None if res is None else _f32(res, (n, k, ho, wo))
+    out = np.empty(coords.shape[0], dtype=np.float32)
+    lib.tt_oracle_conv2d_points(_ptr(x), _ptr(w), _ptr(bias), _ptr(res),
+                                coords.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), _ptr(out), coords.shape[0], n, c,
+                                h, wd, k, r, s, stride[0], stride[1], pad[0], pad[1], act)
+    return out
 
 
 def dense(x, w, bias=None, act=ACT_NONE, acc64=True):

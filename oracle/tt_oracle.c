@@ -117,6 +117,40 @@ void tt_oracle_conv2d(const float *x, const float *w, const float *bias, const f
 }
 
 /*
+ * The same definition evaluated at selected output coordinates only (coords: npts x 4 ints
+ * n, k, p, q), for checks at sizes where the whole tensor would take too long.
+ */
+void tt_oracle_conv2d_points(const float *x, const float *w, const float *bias, const float *res, const int *coords,
+                             float *out, long long npts, int N, int C, int H, int W, int K, int R, int S,
+                             int stride_h, int stride_w, int pad_h, int pad_w, int act)
+{
+    const int Ho = out_extent(H, R, stride_h, pad_h);
+    const int Wo = out_extent(W, S, stride_w, pad_w);
+    (void)N;
+#pragma omp parallel for schedule(static)
+    for (long long i = 0; i < npts; ++i) {
+        const int n = coords[4 * i], k = coords[4 * i + 1], p = coords[4 * i + 2], q = coords[4 * i + 3];
+        double acc = 0.0;
+        for (int c = 0; c < C; ++c)
+            for (int r = 0; r < R; ++r) {
+                const int ih = p * stride_h + r - pad_h;
+                for (int s = 0; s < S; ++s) {
+                    const int iw = q * stride_w + s - pad_w;
+                    if (ih < 0 || ih >= H || iw < 0 || iw >= W)
+                        continue;
+                    acc += (double)x[(((size_t)n * C + c) * H + ih) * W + iw] *
+                           (double)w[(((size_t)k * C + c) * R + r) * S + s];
+                }
+            }
+        if (bias)
+            acc += (double)bias[k];
+        if (res)
+            acc += (double)res[(((size_t)n * K + k) * Ho + p) * Wo + q];
+        out[i] = (float)activate(acc, act);
+    }
+}
+
+/*
  * y[m,o] = act( bias[o] + sum_i x[m,i] * w[o,i] );  x: [M,I], w: [O,I] (out, in), y: [M,O].
  */
 void tt_oracle_dense(const float *x, const float *w, const float *bias, float *y, int M, int O, int I,

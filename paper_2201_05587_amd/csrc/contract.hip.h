@@ -145,6 +145,25 @@ template <int DT> __device__ __forceinline__ u32x4 shift_elems(const u32x4 &v, i
 }
 __device__ __forceinline__ uint32_t shift32(uint32_t x, int bits) { return bits >= 0 ? x << bits : x >> -bits; }
 
+// shift_elems for the repair of a vector that hung over a row edge: one element either way is the
+// common case (3x3 filters with padding 1) and costs four byte-align operations; wider shifts take
+// the general path.
+template <int DT> __device__ __forceinline__ u32x4 shift_edge(const u32x4 &v, int elems)
+{
+    if constexpr (DT == TT_F32) {
+        if (elems == 1) return u32x4{0u, v[0], v[1], v[2]};
+        if (elems == -1) return u32x4{v[1], v[2], v[3], 0u};
+    } else {
+        if (elems == 1)
+            return u32x4{v[0] << 16, __builtin_amdgcn_alignbyte(v[1], v[0], 2), __builtin_amdgcn_alignbyte(v[2], v[1], 2),
+                         __builtin_amdgcn_alignbyte(v[3], v[2], 2)};
+        if (elems == -1)
+            return u32x4{__builtin_amdgcn_alignbyte(v[1], v[0], 2), __builtin_amdgcn_alignbyte(v[2], v[1], 2),
+                         __builtin_amdgcn_alignbyte(v[3], v[2], 2), v[3] >> 16};
+    }
+    return shift_elems<DT>(v, elems);
+}
+
 // Zero the elements of a 16-byte item at positions >= keep (0 <= keep; keep >= CH keeps all).
 template <int DT> __device__ __forceinline__ u32x4 keep_first(u32x4 v, int keep)
 {
@@ -189,16 +208,21 @@ template <int DT, int ROWS, int TK, int THREADS> struct RowKLoader {
     static __device__ __forceinline__ void store(const State &st, unsigned char *lds, int K, int row0, int rows_total,
                                                  int k0, int k_end, int tid)
     {
+        // Whole tile inside the matrix and the slice inside the K range (the usual case, the same for
+        // every thread of the workgroup): the registers go to LDS as they are.
+        const bool interior = row0 + ROWS <= rows_total && k0 + TK <= k_end;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int c = tid + i * THREADS;
             if (TOTAL % THREADS != 0 && c >= TOTAL) continue;
             const int r = c / CPR, kc = c % CPR;
-            const int gk = k0 + kc * CH;
-            const int back = gk - min(gk, K - CH); // how far the load was moved back
             u32x4 v = st.raw[i];
-            if (back > 0 || gk + CH > k_end) v = keep_first<DT>(shift_elems<DT>(v, -back), k_end - gk);
-            if (row0 + r >= rows_total) v = u32x4{0u, 0u, 0u, 0u};
+            if (!interior) {
+                const int gk = k0 + kc * CH;
+                const int back = gk - min(gk, K - CH); // how far the load was moved back
+                if (back > 0 || gk + CH > k_end) v = keep_first<DT>(shift_elems<DT>(v, -back), k_end - gk);
+                if (row0 + r >= rows_total) v = u32x4{0u, 0u, 0u, 0u};
+            }
             *reinterpret_cast<u32x4 *>(lds + r * ROWB + kc * 16) = v;
         }
     }
@@ -365,8 +389,9 @@ template <int DT, int TM, int TK, int THREADS, int LEN, int VB> struct ConvTileL
             const uint32_t fix = st.fix[i];
             if constexpr (VB == 16) {
                 const int code = (int)(fix & 15u);
-                v = shift_elems<DT>(u32x4{st.raw[i][0], st.raw[i][1], st.raw[i][2], st.raw[i][3]}, code - 8);
+                v = u32x4{st.raw[i][0], st.raw[i][1], st.raw[i][2], st.raw[i][3]};
                 if (code == 0) v = u32x4{0u, 0u, 0u, 0u};
+                if (code != 0 && code != 8) v = shift_edge<DT>(v, code - 8); // only lanes at a row edge
             } else if constexpr (VB == 4) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -419,14 +444,17 @@ template <int DT, int TN, int TK, int THREADS, int LEN> struct KRowTileLoader {
     {
         const int ng = tid % NG, kl0 = tid / NG;
         const int n = n0 + ng * G;
-        const int back = n - min(n, N - G);
+        const bool interior = n0 + TN <= N && k0 + TK <= k_end; // same for every thread of the workgroup
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int kl = kl0 + i * KSTEP;
             if (KSTEP * NL > TK && kl >= TK) continue;
             u32x4 v = st.raw[i];
-            if (back > 0) v = keep_first<DT>(shift_elems<DT>(v, -back), N - n);
-            if (k0 + kl >= k_end || n >= N) v = u32x4{0u, 0u, 0u, 0u};
+            if (!interior) {
+                const int back = n - min(n, N - G);
+                if (back > 0) v = keep_first<DT>(shift_elems<DT>(v, -back), N - n);
+                if (k0 + kl >= k_end || n >= N) v = u32x4{0u, 0u, 0u, 0u};
+            }
             *reinterpret_cast<u32x4 *>(lds + ((size_t)kl * LEN + ng * G) * sizeof(E)) = v;
         }
     }

@@ -63,6 +63,13 @@ def check_kernel(kernel: wl.Kernel, scheds, seed=1234, ref=None):
                 assert dk.run(s) == want, (kernel.name, s)
                 outs.append(None)
                 continue
+        if s is not None:
+            plan = api.tt_schedule_apply(s, kernel.cls, kernel.shape)
+            if plan.sketch == api.TT_SK_MFMA and plan.variant_id < 0:
+                # a valid plan no compiled kernel implements: refused, nothing launched
+                assert dk.run(s) == api.TT_ERR_UNSUPPORTED, (kernel.name, s)
+                outs.append(None)
+                continue
         got = run_gpu(dk, s)
         assert_close(got, ref, kernel.shape.dtype, f"{kernel.name} {s}")
         outs.append(got)

@@ -257,3 +257,18 @@ def test_bf16_rounding_matches_library_conversion():
     a = rng(12).standard_normal(200000).astype(np.float32) * 10.0
     ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
     np.testing.assert_array_equal(ops.round_to_bf16(a), ref)
+
+
+def test_conv_points_agree_with_the_full_tensor():
+    g = rng(13)
+    x = g.uniform(-1, 1, (2, 5, 9, 8)).astype(np.float32)
+    w = g.standard_normal((6, 5, 3, 3)).astype(np.float32)
+    b = g.uniform(-1, 1, 6).astype(np.float32)
+    full = ops.conv2d(x, w, b, None, (2, 1), (1, 1), ops.ACT_RELU)
+    res = g.uniform(-1, 1, full.shape).astype(np.float32)
+    full = ops.conv2d(x, w, b, res, (2, 1), (1, 1), ops.ACT_RELU)
+    coords = np.array(list(itertools.product(range(2), range(6), range(full.shape[2]), range(full.shape[3]))), dtype=np.int32)
+    pts = ops.conv2d_points(x, w, coords, b, res, (2, 1), (1, 1), ops.ACT_RELU)
+    np.testing.assert_array_equal(pts, full.reshape(-1))
+    with pytest.raises(ValueError):
+        ops.conv2d_points(x, w, np.array([[0, 0, 99, 0]]), b)
