@@ -29,8 +29,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
  *     operator entry points only enqueue work on it and return; the caller
  *     synchronises.  tt_transfer_sweep synchronises the stream itself;
- *   - tensors are dense, row-major in the order written (NCHW activations, KCRS
- *     filters); element type is tt_dtype of the shape; bias is always the same
+ *   - tensors are dense, row-major in the order written (channels-last: NHWC
+ *     activations, KRSC filters); element type is tt_dtype of the shape; bias is always the same
  *     type as the activations; accumulation is always float32;
  *   - an operator entry point given a schedule that is invalid for the shape
  *     returns the error and writes nothing: falling back to the default schedule
@@ -100,8 +100,10 @@ typedef enum tt_sketch {
     TT_SK_DIRECT = 3  /* any class: one thread per output, the unscheduled loop nest                     */
 } tt_sketch;
 
-/* NCHW activations [n,c,h,w]; KCRS filters [k,c,r,s] ([c,1,r,s] for depthwise, with k == c).
- * Cross-correlation, zero padding, dilation 1, groups 1 (Algorithm 2). */
+/* A convolution's sizes.  Memory is channels-last: activations [n,h,w,c], filters [k,r,s,c]
+ * ([r,s,c] for depthwise, with k == c), outputs [n,Ho,Wo,k].  The operator is Algorithm 2's:
+ * cross-correlation, zero padding, dilation 1, groups 1; only the storage order differs from the
+ * paper's NCHW listing, so that the reduction axis is contiguous for the matrix cores. */
 typedef struct tt_conv_shape {
     int32_t n, c, h, w, k, r, s, stride_h, stride_w, pad_h, pad_w;
     int32_t dtype; /* tt_dtype */
@@ -119,7 +121,8 @@ typedef struct tt_gemm_shape {
  * depends on the size of the kernel it was tuned for, so it can be re-applied
  * to any kernel of its class (Section 4.1's Split(N, N/8, 8) form).
  *
- * Meaning per sketch (GEMM view: conv M = n*Ho*Wo, N = k, K = c*r*s; dense and
+ * Meaning per sketch (GEMM view: conv M = n*Ho*Wo, N = k, K = r * (s*c rounded up to whole
+ * 16-byte items), which is c*r*s whenever s*c fills whole items; dense and
  * batch matmul M, N, K per batch; depthwise M = Ho, N = Wo, "K" = n*c planes):
  *   TT_SK_MFMA   tile_m x tile_n x tile_k workgroup tile (Split level 1, powers of two 16..256,
  *                tile_k in 16/32/64/128); wave_m x wave_n wave tile (Split level 2); mfma = edge
@@ -213,11 +216,18 @@ int tt_plan_tile(const tt_plan *plan, int64_t wg, int32_t out[8]);
 int tt_debug_tile_map(const tt_plan *plan, int32_t *out_dev, void *stream);
 
 /*
+ * Debug: the quotient n / d as the kernels compute it (one widening multiply by a precomputed
+ * reciprocal, used to turn an output-pixel index into image, row and column), evaluated on the
+ * host.  Defined for 0 <= n < 2^31 and 1 <= d < 2^31; returns -1 outside that range.
+ */
+int64_t tt_debug_fast_div(uint32_t n, uint32_t d);
+
+/*
  * conv2d (+bias) (+residual) (+activation) as an implicit GEMM (Algorithm 2; Table 1
  * classes A, E, F).  cls selects the epilogue: TT_CONV2D_ADD (bias, none),
  * TT_CONV2D_BIAS_RELU, TT_CONV2D_BIAS_ADD_RELU (residual required, same layout
- * and type as y), TT_CONV2D_BIAS_RELU6.  x [n,c,h,w], w [k,c,r,s], bias [k],
- * y [n,k,Ho,Wo], Ho = (h + 2 pad_h - r) / stride_h + 1.
+ * and type as y), TT_CONV2D_BIAS_RELU6.  x [n,h,w,c], w [k,r,s,c], bias [k],
+ * y [n,Ho,Wo,k], Ho = (h + 2 pad_h - r) / stride_h + 1.
  */
 int tt_conv2d_bias_relu(const void *x, const void *w, const void *bias, const void *residual, void *y,
                         const tt_conv_shape *shape, int cls, const tt_schedule *sched, void *ws,
@@ -235,7 +245,8 @@ int tt_dense_bias_relu(const void *x, const void *w, const void *bias, void *y, 
 int tt_batch_matmul(const void *a, const void *b, void *c, const tt_gemm_shape *shape,
                     const tt_schedule *sched, void *ws, size_t ws_bytes, void *stream);
 
-/* Depthwise 3x3 conv + bias + clamp[0,6]; w [c,1,3,3]; class TT_DWCONV_BIAS_RELU6; float32 only. */
+/* Depthwise 3x3 conv + bias + clamp[0,6]; x [n,h,w,c], w [3,3,c], y [n,Ho,Wo,c]; class
+ * TT_DWCONV_BIAS_RELU6; float32 only. */
 int tt_dwconv(const void *x, const void *w, const void *bias, void *y, const tt_conv_shape *shape,
               const tt_schedule *sched, void *stream);
 

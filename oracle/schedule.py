@@ -198,7 +198,11 @@ def gemm_extents(cls: int, shape: dict):
             if shape["k"] != shape["c"]:
                 return None
             return (1, ho, wo, shape["n"] * shape["c"])
-        return (1, shape["n"] * ho * wo, shape["k"], shape["c"] * shape["r"] * shape["s"])
+        # reduction = filter rows x the run of S * C elements a filter row covers contiguously in an
+        # NHWC image row, the run rounded up to whole 16-byte items
+        per_item = 4 if shape["dtype"] == DT_F32 else 8
+        runp = ceil_div(shape["s"] * shape["c"], per_item) * per_item
+        return (1, shape["n"] * ho * wo, shape["k"], shape["r"] * runp)
     if shape.get("kind") != "gemm":
         return None
     for f in ("batch", "m", "n", "k"):
@@ -214,11 +218,11 @@ def gemm_extents(cls: int, shape: dict):
 def staged_tile_bytes(cls: int, shape: dict, rec: dict) -> int:
     """LDS bytes of one pipeline stage (resource model of the matrix-core sketch).
 
-    Operands contiguous along K are staged row-major, each row padded by 16 bytes.
-    Operands contiguous along the output axis (NCHW activations; the [K][N] matrix
-    of a non-transposed batch matmul) are staged K-major; their rows are padded so
-    that the row length is 32 mod 64 elements for bf16, and by 8 (32-wide block)
-    or 4 (16-wide block) elements for fp32.
+    Operands contiguous along K (NHWC activations and KRSC filters included) are
+    staged row-major, each row padded by 16 bytes.  The [K][N] matrix of a
+    non-transposed batch matmul is staged K-major; its rows are padded so that the
+    row length is 32 mod 64 elements for bf16, and by 8 (32-wide block) or 4
+    (16-wide block) elements for fp32.
     """
     elem = 4 if shape["dtype"] == DT_F32 else 2
     tm, tn, tk = rec["tile_m"], rec["tile_n"], rec["tile_k"]
@@ -233,9 +237,7 @@ def staged_tile_bytes(cls: int, shape: dict, rec: dict) -> int:
             pad = 8 if rec["mfma"] == 32 else 4
         return tk * (cols + pad) * elem
 
-    if cls in CONV_CLASSES:
-        return k_major(tm) + row_major(tn)
-    if shape["trans_b"]:
+    if cls in CONV_CLASSES or shape["trans_b"]:
         return row_major(tm) + row_major(tn)
     return row_major(tm) + k_major(tn)
 
@@ -357,7 +359,7 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
             lds = tk * rows * cols * elem
         if lds > LDS_BUDGET:
             return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
-        ev = pow2_dividing(min(vmax, rec["wave_n"]), N)
+        ev = 1  # a lane owns one plane and planes are the contiguous (NHWC) axis
         grid = tiles_m * tiles_n * k_tiles
         if grid >= 2 ** 31:
             return _fail(plan, ERR_INVALID_SCHEDULE, R_GRID)
@@ -391,18 +393,9 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
     if lds > LDS_BUDGET:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
     if cls in CONV_CLASSES:
-        ho = conv_out(shape["h"], shape["r"], shape["stride_h"], shape["pad_h"])
-        wo = conv_out(shape["w"], shape["s"], shape["stride_w"], shape["pad_w"])
-        pointwise = (shape["r"] == 1 and shape["s"] == 1 and shape["pad_h"] == 0 and shape["pad_w"] == 0
-                     and shape["stride_h"] == 1 and shape["stride_w"] == 1)
-        if pointwise:
-            eva = pow2_dividing(vmax, shape["h"] * shape["w"])
-        elif shape["stride_w"] == 1:
-            eva = pow2_dividing(vmax, wo)
-        else:
-            eva = 1
-        evb = pow2_dividing(vmax, K)
-        evc = pow2_dividing(vmax, ho * wo)
+        # vectors run along the channel axis of both operands and along the output channels
+        eva = evb = pow2_dividing(vmax, shape["c"])
+        evc = pow2_dividing(vmax, N)
     else:
         eva = pow2_dividing(vmax, K)
         evb = pow2_dividing(vmax, K) if shape["trans_b"] else pow2_dividing(vmax, N)
@@ -475,11 +468,10 @@ def default_schedule(cls: int, shape: dict) -> dict:
     if cls == CLS_DWCONV_BIAS_RELU6:
         if dt != DT_F32:
             return direct
-        tn = min(32, _pow2_floor(N))
-        tm = min(8, _pow2_floor(M))
-        per_plane = tm * tn
-        tk = max(1, 256 // per_plane)
-        if tk > K or (tk * per_plane) % 64 or tk * per_plane < 64:
+        tk = min(64, _pow2_floor(K))
+        tn = min(256 // tk, _pow2_floor(N))
+        tm = min(256 // (tk * tn), _pow2_floor(M))
+        if (tk * tm * tn) % 64 or tk * tm * tn < 64:
             return direct
         return record(cls, SK_DWCONV, tm, tn, tk, 1, 1, 0, 1, 0, 1, 1, 1)
     kmin = 16 if dt == DT_F32 else 32

@@ -86,7 +86,7 @@ class tt_sweep_row(Structure):
 
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
-           "tt_debug_tile_map", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
+           "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
            "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info")
 
 
@@ -125,8 +125,10 @@ def _load():
     lib.tt_sweep_select.argtypes = [POINTER(c_int32), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
                                     POINTER(c_double), ctypes.c_int, POINTER(tt_sweep_row)]
     for name in EXPORTS:
-        if name not in ("tt_status_name", "tt_last_error"):
+        if name not in ("tt_status_name", "tt_last_error", "tt_debug_fast_div"):
             getattr(lib, name).restype = ctypes.c_int
+    lib.tt_debug_fast_div.restype = c_int64
+    lib.tt_debug_fast_div.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
     return lib
 
 

@@ -13,10 +13,9 @@
 // takes elements [g*CH, g*CH+CH) of each K granule); both operands use the same
 // permutation, so the sum is unchanged.
 //
-// Matrix-core rows are mapped to the axis that is NOT contiguous in the output
-// and columns to the contiguous one, so the 32 (16) lanes of a block row write
-// neighbouring addresses: conv (NCHW) -> rows = output channels, columns =
-// pixels; dense / batch matmul (row-major [M][N]) -> rows = M, columns = N.
+// Every output is a row-major [M][N] matrix: dense and batch matmul as they are,
+// conv2d because activations are NHWC, so the flattened pixel index is M and the
+// output channel is N.  Matrix-core rows map to M and columns to N.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -116,22 +115,16 @@ template <> struct Mma<TT_F32, 16> {
 
 // ---- global -> register loaders ---------------------------------------------------------------------------------
 //
-// All loaders follow one rule: a fetch only ISSUES loads.  Every load is unconditional (an
-// address that would fall outside the tensor is replaced by a safe one inside it) and lands in a
-// register nothing reads until the slice is written to LDS, so the loads of slice t+1 stay in
-// flight during the matrix work of slice t.  Zero padding, tails and edge repair are applied by
-// the store step, which recomputes (or has kept) which parts of each 16-byte item are real.
-// There is one straight-line code path per kernel: how the activations are fetched is a
-// template parameter, not a run-time branch.
+// All loaders follow one rule: a fetch only ISSUES loads.  Every load is unconditional and lands
+// in a register nothing reads until the slice is written to LDS, so the loads of slice t+1 stay
+// in flight during the matrix work of slice t.  The row loader replaces an address that would fall
+// outside the matrix by a safe one inside it and repairs tails in the store step; the gathering
+// loader uses bounds-checked buffer loads, which return zero for an offset outside the tensor, so
+// padding and tails cost one select on the offset and nothing afterwards.  There is one
+// straight-line code path per kernel: how the operands are fetched is a template parameter.
 
 // Unconditional loads into registers (addresses need only element alignment).
 __device__ __forceinline__ void load16(u32x4 &dst, const void *p) { __builtin_memcpy(&dst, p, 16); }
-__device__ __forceinline__ void load4(u32x4 &v, int at, const void *p)
-{
-    uint32_t t;
-    __builtin_memcpy(&t, p, 4);
-    v[at] = t;
-}
 
 // Shift the 16-byte value by whole elements: positive = towards higher element indices; zero fill.
 template <int DT> __device__ __forceinline__ u32x4 shift_elems(const u32x4 &v, int elems)
@@ -142,26 +135,6 @@ template <int DT> __device__ __forceinline__ u32x4 shift_elems(const u32x4 &v, i
     x = elems >= 0 ? (x << (EB * elems)) : (x >> (EB * -elems));
     u32x4 r = {(uint32_t)x, (uint32_t)(x >> 32), (uint32_t)(x >> 64), (uint32_t)(x >> 96)};
     return r;
-}
-__device__ __forceinline__ uint32_t shift32(uint32_t x, int bits) { return bits >= 0 ? x << bits : x >> -bits; }
-
-// shift_elems for the repair of a vector that hung over a row edge: one element either way is the
-// common case (3x3 filters with padding 1) and costs four byte-align operations; wider shifts take
-// the general path.
-template <int DT> __device__ __forceinline__ u32x4 shift_edge(const u32x4 &v, int elems)
-{
-    if constexpr (DT == TT_F32) {
-        if (elems == 1) return u32x4{0u, v[0], v[1], v[2]};
-        if (elems == -1) return u32x4{v[1], v[2], v[3], 0u};
-    } else {
-        if (elems == 1)
-            return u32x4{v[0] << 16, __builtin_amdgcn_alignbyte(v[1], v[0], 2), __builtin_amdgcn_alignbyte(v[2], v[1], 2),
-                         __builtin_amdgcn_alignbyte(v[3], v[2], 2)};
-        if (elems == -1)
-            return u32x4{__builtin_amdgcn_alignbyte(v[1], v[0], 2), __builtin_amdgcn_alignbyte(v[2], v[1], 2),
-                         __builtin_amdgcn_alignbyte(v[3], v[2], 2), v[3] >> 16};
-    }
-    return shift_elems<DT>(v, elems);
 }
 
 // Zero the elements of a 16-byte item at positions >= keep (0 <= keep; keep >= CH keeps all).
@@ -228,14 +201,144 @@ template <int DT, int ROWS, int TK, int THREADS> struct RowKLoader {
     }
 };
 
-// ---- K-major tiles: operands whose memory is contiguous along the OUTPUT axis, not along K -----------------------
+
+// ---- gathered tiles: conv2d as an implicit GEMM over NHWC activations -------------------------------------------
 //
-// NCHW activations seen as the implicit-GEMM matrix (K = (c, r, s); consecutive output pixels of
-// a row are consecutive input pixels) and the [K][N] operand of a non-transposed batch matmul.
-// The tile is kept in LDS as T[k][x], x contiguous, so global vectors are copied as they are.
-// Matrix-core fragments (8 consecutive K per lane for bf16) come out of the transposing LDS read
-// of gfx950: within 16 lanes, lane i supplies the address of 4 consecutive x of K-row i/4 and
-// receives the 4 K-rows of column i.  fp32 fragments are four 4-byte reads.
+// Row m of the implicit matrix is output pixel (image, p, q); the reduction index is
+// k = r * runp + j, with r the filter row and j the position inside the RUN of S * C elements that
+// one filter row covers.  In an NHWC image row those S * C elements are contiguous, and so they are
+// in a KRSC filter, so element (m, k) sits at  origin(m) + r * row_stride + j  where origin(m) is
+// the (possibly negative) element offset of tap (0, 0), channel 0.  It is real when filter row r
+// falls inside the image (one bit per r, kept per row of the tile) and j inside [jlo, jhi), the
+// part of the run that falls inside the image row; everything else is zero padding.
+//
+// With VEC an item is one 16-byte load: C is a multiple of the items' element count, so an item
+// lies inside one pixel and is real or padding as a whole.  Without VEC (the 3-channel stem) an
+// item is gathered element by element, each with its own bounds, and the run is padded up to
+// whole items (runp > run).  The same loader reads the filter matrix in that case (WEIGHTS):
+// rows are output channels, origin = n * R * run, every filter row is real and j < run.
+//
+// All rows a thread loads share one chunk of the slice (THREADS is a multiple of the chunks per
+// row), so (r, j) is one pair per thread, advanced by add-and-carry from slice to slice.
+
+constexpr uint32_t kOutOfRange = 0x80000000u; // byte offset no tensor reaches: such a load returns zero
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    // raw buffer (stride 0), 32-bit data format: offsets are bytes, checked against `bytes`
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+
+template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct GatherLoader {
+    using E = typename ElemOf<DT>::type;
+    static constexpr int CH = ElemOf<DT>::CH, ES = (int)sizeof(E), CPR = TK / CH, TOTAL = ROWS * CPR;
+    static constexpr int NL = (TOTAL + THREADS - 1) / THREADS, STEP = THREADS / CPR;
+    static constexpr int ROWB = (TK + CH) * ES;
+    static_assert(THREADS % CPR == 0, "a thread's items must share one chunk of the slice");
+    struct State {
+        int32_t origin[NL];  // element offset of (tap (0,0), channel 0) / of the filter's first element
+        uint32_t rmask[NL];  // bit r set: filter row r of this tile row is real (0 for rows past the matrix)
+        int32_t jlo[NL], jhi[NL];
+        int32_t r, j, dr, dj, runp, row_stride;
+        u32x4 raw[NL];
+    };
+
+    static __device__ __forceinline__ void init(State &st, const ContractArgs &g, int row0, int k0, int tid)
+    {
+        const int chunk = tid % CPR, first = tid / CPR;
+        const int kk = k0 + chunk * CH;
+        st.runp = g.runp;
+        st.r = kk / g.runp;
+        st.j = kk - st.r * g.runp;
+        st.dr = TK / g.runp;
+        st.dj = TK - st.dr * g.runp;
+        st.row_stride = WEIGHTS ? g.run : g.W * g.C;
+        const uint32_t all_rows = g.R >= 32 ? 0xffffffffu : ((1u << g.R) - 1u);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int row = first + i * STEP;
+            const int m = row0 + row;
+            const bool live = (TOTAL % THREADS == 0 || row < ROWS) && m < (WEIGHTS ? g.N : g.M);
+            if constexpr (WEIGHTS) {
+                st.origin[i] = live ? m * g.R * g.run : 0;
+                st.rmask[i] = live ? all_rows : 0u;
+                st.jlo[i] = 0;
+                st.jhi[i] = g.run;
+            } else {
+                const uint32_t um = live ? (uint32_t)m : 0u;
+                const uint32_t img = fast_div(um, g.div_hw);
+                const uint32_t rem = um - img * (uint32_t)(g.Ho * g.Wo);
+                const uint32_t p = fast_div(rem, g.div_wo), q = rem - p * (uint32_t)g.Wo;
+                const int ih0 = (int)p * g.stride_h - g.pad_h, iw0 = (int)q * g.stride_w - g.pad_w;
+                st.origin[i] = (((int)img * g.H + ih0) * g.W + iw0) * g.C;
+                // filter rows [lo, hi) read inside the image
+                const int lo = max(0, -ih0), hi = min(g.R, g.H - ih0);
+                const uint32_t below_hi = hi >= 32 ? 0xffffffffu : ((1u << max(hi, 0)) - 1u);
+                const uint32_t below_lo = (1u << min(lo, 31)) - 1u;
+                st.rmask[i] = (live && hi > lo) ? (below_hi & ~below_lo) : 0u;
+                st.jlo[i] = max(0, -iw0) * g.C;
+                st.jhi[i] = min(g.S, g.W - iw0) * g.C;
+            }
+        }
+    }
+
+    // Issue the loads of the current slice, then step (r, j) to the next one.
+    static __device__ __forceinline__ void load(State &st, __amdgpu_buffer_rsrc_t rsrc, int R)
+    {
+        const int kterm = st.r * st.row_stride + st.j;
+        const bool r_ok = st.r < R;
+        const int rbit = st.r & 31;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const bool row_ok = r_ok && ((st.rmask[i] >> rbit) & 1u);
+            const uint32_t at = (uint32_t)(st.origin[i] + kterm) * (uint32_t)ES;
+            if constexpr (VEC) {
+                const bool ok = row_ok && st.j >= st.jlo[i] && st.j < st.jhi[i];
+                st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ok ? at : kOutOfRange, 0, 0);
+            } else {
+#pragma unroll
+                for (int e = 0; e < CH; ++e) {
+                    const bool ok = row_ok && st.j + e >= st.jlo[i] && st.j + e < st.jhi[i];
+                    const uint32_t off = ok ? at + (uint32_t)(e * ES) : kOutOfRange;
+                    if constexpr (DT == TT_F32) {
+                        st.raw[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0);
+                    } else {
+                        const uint32_t v = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, off, 0, 0);
+                        if (e % 2 == 0)
+                            st.raw[i][e / 2] = v;
+                        else
+                            st.raw[i][e / 2] |= v << 16;
+                    }
+                }
+            }
+        }
+        st.j += st.dj;
+        st.r += st.dr;
+        if (st.j >= st.runp) {
+            st.j -= st.runp;
+            st.r += 1;
+        }
+    }
+
+    static __device__ __forceinline__ void store(const State &st, unsigned char *lds, int tid)
+    {
+        const int chunk = tid % CPR, first = tid / CPR;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int row = first + i * STEP;
+            if (TOTAL % THREADS != 0 && row >= ROWS) continue;
+            *reinterpret_cast<u32x4 *>(lds + row * ROWB + chunk * 16) = st.raw[i];
+        }
+    }
+};
+
+// ---- K-major tiles: the [K][N] operand of a non-transposed batch matmul ------------------------------------------
+//
+// Memory is contiguous along the output axis N, not along K.  The tile is kept in LDS as T[k][n],
+// n contiguous, so global vectors are copied as they are.  Matrix-core fragments (8 consecutive K
+// per lane for bf16) come out of the transposing LDS read of gfx950: within 16 lanes, lane i
+// supplies the address of 4 consecutive n of K-row i/4 and receives the 4 K-rows of column i.
+// fp32 fragments are four 4-byte reads.
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -246,177 +349,7 @@ template <int DT, int ROWS, int MF> struct KMajorRow {
     static constexpr int LEN = ROWS + PAD;
 };
 
-// Implicit-GEMM activation tile, K-major.  An item is one K-row times G = 16 bytes of consecutive
-// output pixels, fetched as 16 / VB loads of VB bytes: the whole item when a row of output
-// pixels is a multiple of G and the stride is 1 (VB = 16), pairs of bf16 pixels when rows are
-// even (VB = 4), else single pixels (VB = element size).
-//
-// Address generation is kept off the critical path.  What depends only on the thread's pixels is
-// computed once per workgroup: the element offset of filter tap (0, 0), one bit per filter row
-// saying whether that row falls inside the image, and one 4-bit code per filter column saying
-// whether the sub-vector is inside the row, outside, or hangs over its left or right end (then
-// the load is moved back inside and the code is the element shift that repairs it).  What depends
-// only on K - (channel, filter row, filter column) - advances by add-and-carry, never by division.
-template <int DT, int TM, int TK, int THREADS, int LEN, int VB> struct ConvTileLoader {
-    using E = typename ElemOf<DT>::type;
-    static constexpr int ES = (int)sizeof(E);
-    static constexpr int G = ElemOf<DT>::CH;              // pixels per item
-    static constexpr int V = VB / ES;                      // pixels per load
-    static constexpr int NS = 16 / VB;                     // loads per item
-    static constexpr int MG = TM / G;                      // items per K-row
-    static constexpr int KSTEP = THREADS / MG;             // K-rows between a thread's items
-    static constexpr int NL = (TK + KSTEP - 1) / KSTEP;    // items per thread and slice
-    static_assert(MG >= 1 && MG <= THREADS, "tile_m does not fit the workgroup");
-    static_assert(VB == 16 || VB == 4 || VB == ES, "unsupported activation fetch width");
-
-    struct Mixed { // a K index as (channel, filter row, filter column)
-        int c, r, s;
-    };
-    struct State {
-        int32_t off[NS];     // per sub-vector: element offset of tap (0, 0) of its first pixel
-        uint32_t rows[NS];   // bit r: filter row r is inside the image
-        uint32_t cols[NS];   // nibble s: 0 = outside, else 8 + element shift to apply after the load
-        uint32_t raw[NL][VB == 2 ? 8 : 4];
-        uint32_t fix[NL];    // nibble j: the code sub-vector j was loaded with
-        Mixed kpos;          // decomposition of the first K-row this thread serves in the next slice
-        Mixed step_item, step_tile;
-    };
-
-    static __device__ __forceinline__ Mixed decompose(int k, int R, int S)
-    {
-        Mixed m;
-        m.c = k / (R * S);
-        const int rem = k - m.c * R * S;
-        m.r = rem / S;
-        m.s = rem - m.r * S;
-        return m;
-    }
-    static __device__ __forceinline__ Mixed advance(Mixed a, const Mixed &d, int R, int S)
-    {
-        a.s += d.s;
-        const int cs = a.s >= S;
-        a.s -= cs ? S : 0;
-        a.r += d.r + cs;
-        const int cr = a.r >= R;
-        a.r -= cr ? R : 0;
-        a.c += d.c + cr;
-        return a;
-    }
-
-    static __device__ __forceinline__ void init(State &st, const ContractArgs &g, int m0, int k_first, int tid)
-    {
-        const int mg = tid % MG;
-        const int hw = g.Ho * g.Wo;
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            st.off[j] = 0;
-            st.rows[j] = 0u;
-            st.cols[j] = 0u;
-            const int m = m0 + mg * G + j * V;
-            if (m >= g.M) continue;
-            const int img = m / hw, pix = m - img * hw;
-            const int p = pix / g.Wo, q = pix - p * g.Wo;
-            const int ih0 = p * g.stride_h - g.pad_h, iw0 = q * g.stride_w - g.pad_w;
-            st.off[j] = (img * g.C * g.H + ih0) * g.W + iw0;
-            uint32_t rows = 0u, cols = 0u;
-            for (int r = 0; r < g.R; ++r)
-                if (ih0 + r >= 0 && ih0 + r < g.H) rows |= 1u << r;
-            for (int s = 0; s < g.S; ++s) {
-                const int iw = iw0 + s;
-                if (iw > -V && iw < g.W) {
-                    const int shift = iw < 0 ? -iw : (iw + V > g.W ? g.W - V - iw : 0);
-                    cols |= (uint32_t)(shift + 8) << (4 * s);
-                }
-            }
-            st.rows[j] = rows;
-            st.cols[j] = cols;
-        }
-        st.kpos = decompose(k_first + tid / MG, g.R, g.S);
-        st.step_item = decompose(KSTEP, g.R, g.S);
-        st.step_tile = decompose(TK, g.R, g.S);
-    }
-
-    // Issue the loads of the slice whose first K index is k0 (slices must be fetched in order).
-    static __device__ __forceinline__ void load(State &st, const E *x, const ContractArgs &g, int k0, int k_end, int tid)
-    {
-        const int kl0 = tid / MG;
-        const int hw_in = g.H * g.W;
-        Mixed kp = st.kpos;
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int kl = kl0 + i * KSTEP;
-            const uint32_t k_ok = (kl < TK) & (k0 + kl < k_end);
-            const int koff = kp.c * hw_in + kp.r * g.W + kp.s;
-            uint32_t fix = 0u;
-#pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                const uint32_t present = k_ok & (st.rows[j] >> kp.r) & 1u;
-                const uint32_t code = present ? (st.cols[j] >> (4 * kp.s)) & 15u : 0u;
-                // nothing to read: point at the start of the tensor, which is always readable
-                const int idx = code ? st.off[j] + koff + (int)code - 8 : 0;
-                fix |= code << (4 * j);
-                const E *p = x + idx;
-                if constexpr (VB == 16) {
-                    u32x4 t;
-                    load16(t, p);
-                    st.raw[i][0] = t[0];
-                    st.raw[i][1] = t[1];
-                    st.raw[i][2] = t[2];
-                    st.raw[i][3] = t[3];
-                } else if constexpr (VB == 4) {
-                    uint32_t t;
-                    __builtin_memcpy(&t, p, 4);
-                    st.raw[i][j] = t;
-                } else {
-                    st.raw[i][j] = *reinterpret_cast<const uint16_t *>(p);
-                }
-            }
-            st.fix[i] = fix;
-            kp = advance(kp, st.step_item, g.R, g.S);
-        }
-        st.kpos = advance(st.kpos, st.step_tile, g.R, g.S);
-    }
-
-    static __device__ __forceinline__ void store(const State &st, unsigned char *lds, int tid)
-    {
-        const int mg = tid % MG, kl0 = tid / MG;
-        constexpr int EB = 8 * ES;
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int kl = kl0 + i * KSTEP;
-            if (KSTEP * NL > TK && kl >= TK) continue;
-            u32x4 v;
-            const uint32_t fix = st.fix[i];
-            if constexpr (VB == 16) {
-                const int code = (int)(fix & 15u);
-                v = u32x4{st.raw[i][0], st.raw[i][1], st.raw[i][2], st.raw[i][3]};
-                if (code == 0) v = u32x4{0u, 0u, 0u, 0u};
-                if (code != 0 && code != 8) v = shift_edge<DT>(v, code - 8); // only lanes at a row edge
-            } else if constexpr (VB == 4) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int code = (int)((fix >> (4 * j)) & 15u);
-                    // fp32: a single element, present or not; bf16: a pair that may need a one-element shift
-                    if constexpr (DT == TT_F32)
-                        v[j] = code != 0 ? st.raw[i][j] : 0u;
-                    else
-                        v[j] = code != 0 ? shift32(st.raw[i][j], EB * (code - 8)) : 0u;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t lo = ((fix >> (8 * j)) & 15u) != 0u ? (st.raw[i][2 * j] & 0xffffu) : 0u;
-                    const uint32_t hi = ((fix >> (8 * j + 4)) & 15u) != 0u ? (st.raw[i][2 * j + 1] << 16) : 0u;
-                    v[j] = lo | hi;
-                }
-            }
-            *reinterpret_cast<u32x4 *>(lds + ((size_t)kl * LEN + mg * G) * sizeof(E)) = v;
-        }
-    }
-};
-
-// [K][N] operand of a non-transposed batch matmul (N >= G): rows of the matrix are rows of the
-// K-major tile.  A 16-byte item that would run past the end of its row is read G elements back
+// Loader of that operand (N >= G): rows of the matrix are rows of the K-major tile.  A 16-byte item that would run past the end of its row is read G elements back
 // from the row end and shifted down afterwards.
 template <int DT, int TN, int TK, int THREADS, int LEN> struct KRowTileLoader {
     using E = typename ElemOf<DT>::type;
@@ -480,18 +413,19 @@ template <int DT, int MF, int LEN> __device__ __forceinline__ u32x4 kmajor_fragm
     }
 }
 
+
 // LDS bytes of one pipeline stage: the A tile followed by the B tile.
 template <int DT, int FAM, int TM, int TN, int TK, int MF> struct StageLayout {
     using E = typename ElemOf<DT>::type;
     static constexpr int CH = ElemOf<DT>::CH, ES = (int)sizeof(E);
     static constexpr int ROWB = (TK + CH) * ES; // row of a K-contiguous tile, padded by 16 bytes
-    static constexpr int LEN_A = KMajorRow<DT, TM, MF>::LEN, LEN_B = KMajorRow<DT, TN, MF>::LEN;
-    static constexpr int A_BYTES = FAM == FAM_CONV ? TK * LEN_A * ES : TM * ROWB;
+    static constexpr int LEN_B = KMajorRow<DT, TN, MF>::LEN;
+    static constexpr int A_BYTES = TM * ROWB;
     static constexpr int B_BYTES = FAM == FAM_GEMM_NN ? TK * LEN_B * ES : TN * ROWB;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
 };
 
-// AM = bytes per activation load of the conv family (16, 4 or the element size); 0 for the others.
+// AM = bytes per gathered load of the conv family (16 or the element size); 0 for the others.
 template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int AM>
 __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(const ContractArgs g)
 {
@@ -500,19 +434,20 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     constexpr int CH = ElemOf<DT>::CH, ES = (int)sizeof(E);
     constexpr int THREADS = (TM / WM) * (TN / WN) * 64;
     constexpr int ROWB = L::ROWB, A_BYTES = L::A_BYTES, STAGE_BYTES = L::STAGE_BYTES;
-    constexpr bool SWAP = FAM == FAM_CONV; // matrix-core rows = N side, columns = M side
-    constexpr int WR = SWAP ? WN : WM, WC = SWAP ? WM : WN;
-    constexpr int NWR = SWAP ? TN / WN : TM / WM; // waves along the matrix-core row axis
-    constexpr int NI = WR / MF, NJ = WC / MF;
+    constexpr int NWR = TM / WM; // waves along M
+    constexpr int NI = WM / MF, NJ = WN / MF;
     constexpr int LG = 64 / MF, KS = CH * LG, NKS = TK / KS;
     constexpr int ACC = MF * MF / 64;
-    constexpr bool C_KMAJOR = FAM != FAM_GEMM_TN;     // the column-side tile is K-major
-    constexpr int LEN_C = SWAP ? L::LEN_A : L::LEN_B; // its padded row length
+    constexpr bool B_KMAJOR = FAM == FAM_GEMM_NN;
+    constexpr bool CONV = FAM == FAM_CONV;
+    constexpr bool CONV_VEC = CONV && AM == 16; // 16-byte gathers of activations, plain rows of filters
+    constexpr bool CONV_ELEM = CONV && AM != 16; // both operands gathered element by element
     static_assert(TK % KS == 0, "tile_k must be a multiple of the K granule");
     using M = Mma<DT, MF>;
     using ALoad = RowKLoader<DT, TM, TK, THREADS>;
-    using AConv = ConvTileLoader<DT, TM, TK, THREADS, L::LEN_A, FAM == FAM_CONV ? AM : 16>;
+    using AGather = GatherLoader<DT, TM, TK, THREADS, CONV_VEC, false>;
     using BLoad = RowKLoader<DT, TN, TK, THREADS>;
+    using BGather = GatherLoader<DT, TN, TK, THREADS, false, true>;
     using BKRow = KRowTileLoader<DT, TN, TK, THREADS, L::LEN_B>;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -525,38 +460,47 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
 
     const E *a_base = static_cast<const E *>(g.a);
     const E *b_base = static_cast<const E *>(g.b);
-    if constexpr (FAM != FAM_CONV) {
+    if constexpr (!CONV) {
         a_base += (int64_t)bidx * g.M * g.K;
         b_base += (int64_t)bidx * g.N * g.K;
     }
 
     // registers holding the slice in flight (only the members of the family in use are live)
-    typename AConv::State a_conv;
+    typename AGather::State a_gat;
+    typename BGather::State b_gat;
     typename BKRow::State b_krow;
     typename ALoad::State a_rows;
     typename BLoad::State b_rows;
-    if constexpr (FAM == FAM_CONV) AConv::init(a_conv, g, tc.m0, tc.k0, tid);
+    __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(g.a, CONV ? g.a_bytes : 0u);
+    __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(g.b, CONV_ELEM ? g.b_bytes : 0u);
+    if constexpr (CONV) AGather::init(a_gat, g, tc.m0, tc.k0, tid);
+    if constexpr (CONV_ELEM) BGather::init(b_gat, g, tc.n0, tc.k0, tid);
 
+    // slices are fetched in order: the gathering loaders step their own position
     auto fetch = [&](int kt) {
         const int k0 = tc.k0 + kt * TK;
-        if constexpr (FAM == FAM_CONV)
-            AConv::load(a_conv, a_base, g, k0, k_end, tid);
+        if constexpr (CONV)
+            AGather::load(a_gat, a_rsrc, g.R);
         else
             ALoad::load(a_rows, a_base, g.K, tc.m0, g.M, k0, tid);
-        if constexpr (FAM == FAM_GEMM_NN)
+        if constexpr (B_KMAJOR)
             BKRow::load(b_krow, b_base, g.N, g.K, tc.n0, k0, tid);
+        else if constexpr (CONV_ELEM)
+            BGather::load(b_gat, b_rsrc, g.R);
         else
             BLoad::load(b_rows, b_base, g.K, tc.n0, g.N, k0, tid);
     };
     auto stash = [&](int stage, int kt) {
         const int k0 = tc.k0 + kt * TK;
         unsigned char *sa = smem + stage * STAGE_BYTES, *sb = sa + A_BYTES;
-        if constexpr (FAM == FAM_CONV)
-            AConv::store(a_conv, sa, tid);
+        if constexpr (CONV)
+            AGather::store(a_gat, sa, tid);
         else
             ALoad::store(a_rows, sa, g.K, tc.m0, g.M, k0, k_end, tid);
-        if constexpr (FAM == FAM_GEMM_NN)
+        if constexpr (B_KMAJOR)
             BKRow::store(b_krow, sb, g.N, tc.n0, k0, k_end, tid);
+        else if constexpr (CONV_ELEM)
+            BGather::store(b_gat, sb, tid);
         else
             BLoad::store(b_rows, sb, g.K, tc.n0, g.N, k0, k_end, tid);
     };
@@ -571,8 +515,8 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
 
     const int wr = wave % NWR, wc = wave / NWR;
     const int lane_r = lane % MF, lane_g = lane / MF;
-    const int r_off = (wr * WR + lane_r) * ROWB + lane_g * 16;
-    const int c_off = (wc * WC + lane_r) * ROWB + lane_g * 16;
+    const int r_off = (wr * WM + lane_r) * ROWB + lane_g * 16;
+    const int c_off = (wc * WN + lane_r) * ROWB + lane_g * 16;
 
     auto k_step = [&](const unsigned char *sr, const unsigned char *sc, int ks) {
         u32x4 rf[NI], cf[NJ];
@@ -581,8 +525,8 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
             rf[i] = *reinterpret_cast<const u32x4 *>(sr + r_off + i * MF * ROWB + ks * KS * ES);
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-            if constexpr (C_KMAJOR)
-                cf[j] = kmajor_fragment<DT, MF, LEN_C>(sc, wc * WC + j * MF, ks * KS, lane);
+            if constexpr (B_KMAJOR)
+                cf[j] = kmajor_fragment<DT, MF, L::LEN_B>(sc, wc * WN + j * MF, ks * KS, lane);
             else
                 cf[j] = *reinterpret_cast<const u32x4 *>(sc + c_off + j * MF * ROWB + ks * KS * ES);
         }
@@ -602,13 +546,12 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
         const bool more = it + 1 < kt_count;
         if (more) fetch(it + 1);
         const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
-        const unsigned char *sr = SWAP ? sb : sa, *sc = SWAP ? sa : sb;
         if (unrolled || NKS == 1) {
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) k_step(sr, sc, ks);
+            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
         } else {
 #pragma unroll 1
-            for (int ks = 0; ks < NKS; ++ks) k_step(sr, sc, ks);
+            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
         }
         if (more) {
             if (!two_stage) __syncthreads();
@@ -626,18 +569,17 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     // sub-vectors the output's row length allows), and stores are fully coalesced.  With split-K
     // the raw partial sums go to the workspace in the same pattern.
     {
-        constexpr int ESTRIDE = WC + (MF == 32 ? 8 : 4);      // floats per staged row (bank-conflict padding)
-        constexpr int CG = WC / 8;                            // 8-column groups per row
+        constexpr int ESTRIDE = WN + (MF == 32 ? 8 : 4);      // floats per staged row (bank-conflict padding)
+        constexpr int CG = WN / 8;                            // 8-column groups per row
         constexpr int ROWS_PER_PASS = 64 / CG;                // rows the 64 lanes cover at once
         constexpr int PASSES = (MF + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
         float *stage = reinterpret_cast<float *>(smem) + wave * (MF * ESTRIDE);
         const bool partial = g.map.eff_split_k > 1;
         const int64_t mn = (int64_t)g.M * g.N;
         float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
-        const int hw = g.Ho * g.Wo;
-        int vc = g.eff_vec_c; // consecutive outputs that are contiguous in memory and all inside or all outside
+        const int vc = g.eff_vec_c; // consecutive outputs of a row that are all inside or all outside the matrix
         const int cg = lane % CG, row_in_pass = lane / CG;
-        const int c0 = wc * WC + cg * 8; // first of this lane's 8 columns inside the workgroup tile
+        const int c0 = wc * WN + cg * 8; // first of this lane's 8 columns inside the workgroup tile
 
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -657,24 +599,14 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
                 const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8);
                 const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
                 float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                const int row = wr * WR + i * MF + row_l;
-                // coordinates: SWAP (conv): row -> output channel n, columns -> pixels m; else row -> m, columns -> n
-                const int fixed = (SWAP ? tc.n0 : tc.m0) + row;
-                if (fixed >= (SWAP ? g.N : g.M)) continue;
-                const int first = (SWAP ? tc.m0 : tc.n0) + c0;
-                const int limit = SWAP ? g.M : g.N;
-                const float bias_row = (SWAP && g.has_bias && !partial) ? load_as_float<DT>(g.bias, fixed) : 0.0f;
+                const int m = tc.m0 + wr * WM + i * MF + row_l;
+                if (m >= g.M) continue;
+                const int first = tc.n0 + c0;
                 // groups of vc consecutive columns
                 for (int e0 = 0; e0 < 8; e0 += vc) {
-                    const int colg = first + e0;
-                    if (colg >= limit) break;
-                    int64_t idx;
-                    if constexpr (SWAP) {
-                        const int img = colg / hw, pix = colg - img * hw;
-                        idx = ((int64_t)img * g.N + fixed) * hw + pix;
-                    } else {
-                        idx = (int64_t)bidx * mn + (int64_t)fixed * g.N + colg;
-                    }
+                    const int n = first + e0;
+                    if (n >= g.N) break;
+                    const int64_t idx = (int64_t)bidx * mn + (int64_t)m * g.N + n;
                     if (partial) {
                         if (vc == 8) {
                             *reinterpret_cast<f32x4 *>(ws + idx) = lo;
@@ -689,14 +621,12 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
                     if (vc == 8 && DT == TT_BF16) {
                         u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
                         if (g.has_res) resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
-                        if (!SWAP && g.has_bias)
-                            biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + colg);
+                        if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
                         u32x4 outv;
 #pragma unroll
                         for (int h = 0; h < 4; ++h) {
-                            float a = val[2 * h] + bias_row + __uint_as_float(biasv[h] << 16) +
-                                      __uint_as_float(resv[h] << 16);
-                            float b = val[2 * h + 1] + bias_row + __uint_as_float(biasv[h] & 0xffff0000u) +
+                            float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
+                            float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) +
                                       __uint_as_float(resv[h] & 0xffff0000u);
                             outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
                                       ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
@@ -708,9 +638,9 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
                             if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
                             f32x4 r = q4 == 0 ? lo : hi;
                             const int64_t at = idx + (q4 * 4 - e0);
-                            f32x4 add = {bias_row, bias_row, bias_row, bias_row};
-                            if (!SWAP && g.has_bias)
-                                add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + colg + (q4 * 4 - e0));
+                            f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
+                            if (g.has_bias)
+                                add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
                             if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
 #pragma unroll
                             for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
@@ -718,8 +648,8 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
                         }
                     } else {
                         for (int e = 0; e < vc; ++e) {
-                            float a = val[e0 + e] + bias_row;
-                            if (!SWAP && g.has_bias) a += load_as_float<DT>(g.bias, colg + e);
+                            float a = val[e0 + e];
+                            if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
                             if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
                             store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
                         }
@@ -735,8 +665,7 @@ int launch_contract(const ContractArgs &args, int grid, int lds_bytes, void *str
 {
     auto kern = contract_kernel<DT, FAM, TM, TN, TK, WM, WN, MF, AM>;
     // the epilogue stages one band of MF rows per wave in the same LDS
-    constexpr int WC_ = FAM == FAM_CONV ? WM : WN;
-    constexpr int EPI_BYTES = (TM / WM) * (TN / WN) * MF * (WC_ + (MF == 32 ? 8 : 4)) * 4;
+    constexpr int EPI_BYTES = (TM / WM) * (TN / WN) * MF * (WN + (MF == 32 ? 8 : 4)) * 4;
     if (lds_bytes < EPI_BYTES) lds_bytes = EPI_BYTES;
     static int raised = 0; // largest dynamic-LDS size this kernel has been enabled for
     if (lds_bytes > 48 * 1024 && lds_bytes > raised) {

@@ -92,10 +92,12 @@ extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bia
     tt_plan plan;
     const int rc = make_plan(sched, cls, shape, ws, ws_bytes, &plan);
     if (rc != TT_OK) return rc;
-    // the matrix-core kernel addresses activations with 32-bit element offsets and keeps one bit per
-    // filter row and four per filter column
-    if (plan.sketch == TT_SK_MFMA &&
-        ((int64_t)shape->n * shape->c * shape->h * shape->w >= (1ll << 31) || shape->r > 32 || shape->s > 8))
+    // the matrix-core kernels address both tensors with 32-bit byte offsets below 2^31 and keep one
+    // bit per filter row
+    const int elem = shape->dtype == TT_F32 ? 4 : 2;
+    const int64_t x_bytes = (int64_t)shape->n * shape->h * shape->w * shape->c * elem;
+    const int64_t w_bytes = (int64_t)shape->k * shape->r * shape->s * shape->c * elem;
+    if (plan.sketch == TT_SK_MFMA && (x_bytes >= (1ll << 31) || w_bytes >= (1ll << 31) || shape->r > 32))
         return TT_ERR_UNSUPPORTED;
     ContractArgs g;
     std::memset(&g, 0, sizeof g);
@@ -119,15 +121,17 @@ extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bia
     g.pad_w = shape->pad_w;
     g.Ho = conv_out(shape->h, shape->r, shape->stride_h, shape->pad_h);
     g.Wo = conv_out(shape->w, shape->s, shape->stride_w, shape->pad_w);
-    if (shape->r == 1 && shape->s == 1 && shape->pad_h == 0 && shape->pad_w == 0 && shape->stride_h == 1 &&
-        shape->stride_w == 1) {
-        // unit-stride pointwise conv: every (h, w) plane is one long row, so vectors may span image rows
-        g.W = shape->h * shape->w;
-        g.H = 1;
-        g.Wo = g.W;
-        g.Ho = 1;
-    }
-    return run_contraction(g, plan, FAM_CONV, stream);
+    const int per_item = 16 / elem;
+    g.run = shape->s * shape->c;
+    g.runp = (g.run + per_item - 1) / per_item * per_item;
+    g.div_hw = make_fastdiv((uint32_t)(g.Ho * g.Wo));
+    g.div_wo = make_fastdiv((uint32_t)g.Wo);
+    g.a_bytes = (uint32_t)x_bytes;
+    g.b_bytes = (uint32_t)w_bytes;
+    int family = FAM_CONV;
+    if (plan.sketch == TT_SK_MFMA && plan.variant_id >= 0 && plan.variant_id < kNumVariants)
+        family = kVariants[plan.variant_id].family; // the dense family for unit-stride 1x1 filters
+    return run_contraction(g, plan, family, stream);
 }
 
 static int gemm_entry(const void *a, const void *b, const void *bias, void *c, const tt_gemm_shape *shape, int cls,
@@ -193,7 +197,6 @@ extern "C" int tt_dwconv(const void *x, const void *w, const void *bias, void *y
     g.pad_w = shape->pad_w;
     g.wave_m = plan.wave_m;
     g.wave_n = plan.wave_n;
-    g.eff_vec = plan.eff_vec_c;
     g.stages = plan.stages;
     g.unroll = plan.eff_unroll;
     if (plan.sketch == TT_SK_DIRECT) return launch_dw_direct(g, plan.grid, stream);

@@ -49,7 +49,11 @@ bool extents_of(int cls, const void *shape, Extents *e, int *dtype)
             *e = {1, ho, wo, (int)planes};
             return true;
         }
-        const int64_t m = (int64_t)s->n * ho * wo, k = (int64_t)s->c * s->r * s->s;
+        // The reduction runs over filter rows times the run of S * C elements a filter row covers
+        // contiguously in an NHWC image row, the run rounded up to whole 16-byte items.
+        const int per_item = s->dtype == TT_F32 ? 4 : 8;
+        const int64_t run = (int64_t)s->s * s->c, runp = (run + per_item - 1) / per_item * per_item;
+        const int64_t m = (int64_t)s->n * ho * wo, k = (int64_t)s->r * runp;
         if (m > INT32_MAX || k > INT32_MAX) return false;
         *e = {1, (int)m, s->k, (int)k};
         return true;
@@ -186,10 +190,11 @@ extern "C" int tt_schedule_default(int cls, const void *shape, tt_schedule *out)
     *out = direct;
     if (cls == TT_DWCONV_BIAS_RELU6) {
         if (dt != TT_F32) return TT_OK;
-        const int tn = std::min(32, pow2_floor(e.N)), tm = std::min(8, pow2_floor(e.M));
-        const int per_plane = tm * tn;
-        const int tk = std::max(1, 256 / per_plane);
-        if (tk > e.K || (tk * per_plane) % 64 || tk * per_plane < 64) return TT_OK;
+        // planes (channels) are the contiguous axis: give them to the lanes first
+        const int tk = std::min(64, pow2_floor(e.K));
+        const int tn = std::min(256 / tk, pow2_floor(e.N)), tm = std::min(256 / (tk * tn), pow2_floor(e.M));
+        const int threads = tk * tm * tn;
+        if (threads % 64 || threads < 64) return TT_OK;
         *out = make_record(cls, TT_SK_DWCONV, tm, tn, tk, 1, 1, 0, 1, 0, 1, 1, 1);
         return TT_OK;
     }
@@ -287,13 +292,11 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
         const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.k_tiles;
         if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
-        const int ev = widest_dividing(std::min(vmax, r.wave_n), e.N);
+        // a lane owns one plane, and planes are the contiguous axis: nothing left to vectorise
         p.eff_split_k = 1;
         p.k_iters = 1;
         p.slabs = p.k_tiles;
-        p.eff_vec_a = ev;
-        p.eff_vec_b = 1;
-        p.eff_vec_c = ev;
+        p.eff_vec_a = p.eff_vec_b = p.eff_vec_c = 1;
         p.eff_unroll = std::min(r.unroll, r.wave_m);
         p.grid = (int)grid;
         p.block = r.tile_k * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
@@ -327,27 +330,23 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     p.eff_split_k = cdiv(p.k_tiles, p.k_iters);
     int trans_b = 1;
     if (!is_conv_class(cls)) trans_b = static_cast<const tt_gemm_shape *>(shape)->trans_b;
-    // Staged tiles.  An operand that is contiguous along K is kept row-major with 16 bytes of row
-    // padding; one that is contiguous along the output axis (NCHW activations, the [K][N] matrix)
-    // is kept K-major with a row padding that depends on the data type and the matrix-core block.
+    // Staged tiles.  An operand that is contiguous along K (NHWC activations and KRSC filters
+    // included) is kept row-major with 16 bytes of row padding; the [K][N] matrix of a non-transposed
+    // batch matmul is kept K-major with a row padding that depends on the data type and the block.
     auto rowk_bytes = [&](int rows) { return (int64_t)rows * (r.tile_k + 16 / elem) * elem; };
     auto kmajor_bytes = [&](int cols) {
         const int pad = dt == TT_BF16 ? (32 + 64 - cols % 64) % 64 : (r.mfma == 32 ? 8 : 4);
         return (int64_t)r.tile_k * (cols + pad) * elem;
     };
-    const int64_t a_bytes = is_conv_class(cls) ? kmajor_bytes(r.tile_m) : rowk_bytes(r.tile_m);
-    const int64_t b_bytes = (!is_conv_class(cls) && !trans_b) ? kmajor_bytes(r.tile_n) : rowk_bytes(r.tile_n);
+    const int64_t a_bytes = rowk_bytes(r.tile_m);
+    const int64_t b_bytes = trans_b ? rowk_bytes(r.tile_n) : kmajor_bytes(r.tile_n);
     const int64_t lds = (int64_t)r.stages * (a_bytes + b_bytes);
     if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
     if (is_conv_class(cls)) {
+        // vectors run along the channel axis of both operands and along the output channels
         const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
-        const int ho = conv_out(s->h, s->r, s->stride_h, s->pad_h), wo = conv_out(s->w, s->s, s->stride_w, s->pad_w);
-        const bool pointwise = s->r == 1 && s->s == 1 && s->pad_h == 0 && s->pad_w == 0 && s->stride_h == 1 &&
-                               s->stride_w == 1;
-        p.eff_vec_a = pointwise ? widest_dividing(vmax, (int64_t)s->h * s->w)
-                                : (s->stride_w == 1 ? widest_dividing(vmax, wo) : 1);
-        p.eff_vec_b = widest_dividing(vmax, e.K);
-        p.eff_vec_c = widest_dividing(vmax, (int64_t)ho * wo);
+        p.eff_vec_a = p.eff_vec_b = widest_dividing(vmax, s->c);
+        p.eff_vec_c = widest_dividing(vmax, e.N);
     } else {
         p.eff_vec_a = widest_dividing(vmax, e.K);
         p.eff_vec_b = trans_b ? widest_dividing(vmax, e.K) : widest_dividing(vmax, e.N);
@@ -361,19 +360,21 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     p.block = 64 * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
     p.lds_bytes = (int)lds;
     p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
-    // How the conv kernels fetch activations: whole 16-byte items when the effective vector width
-    // covers one, pairs of bf16 pixels when rows are even, else single pixels.
-    int amode = 0;
+    // How the conv kernels fetch their operands: 16-byte gathers when the effective vector width
+    // fills an item, else element by element.  A unit-stride 1x1 convolution without padding reads
+    // the activations as a plain [M][C] matrix and runs on the dense family.
+    int amode = 0, family = family_of(cls, trans_b);
     if (is_conv_class(cls)) {
         const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
         const bool pointwise = s->r == 1 && s->s == 1 && s->pad_h == 0 && s->pad_w == 0 && s->stride_h == 1 &&
                                s->stride_w == 1;
-        const int64_t row = pointwise ? (int64_t)s->h * s->w : s->w;
-        const int v = (p.eff_vec_a > row || (!pointwise && s->stride_w != 1)) ? 1 : p.eff_vec_a;
-        amode = v * elem >= 16 ? 16 : (dt == TT_BF16 && v >= 2 ? 4 : elem);
+        amode = p.eff_vec_a * elem == 16 ? 16 : elem;
+        if (pointwise && amode == 16) {
+            family = FAM_GEMM_TN;
+            amode = 0;
+        }
     }
-    p.variant_id =
-        find_variant(dt, family_of(cls, trans_b), r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode);
+    p.variant_id = find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode);
     *plan = p;
     return TT_OK;
 }
@@ -392,6 +393,12 @@ extern "C" int tt_plan_tile(const tt_plan *plan, int64_t wg, int32_t out[8])
     out[6] = c.k0;
     out[7] = c.k_ext;
     return TT_OK;
+}
+
+extern "C" int64_t tt_debug_fast_div(uint32_t n, uint32_t d)
+{
+    if (d < 1 || d >= (1u << 31) || n >= (1u << 31)) return -1;
+    return (int64_t)fast_div(n, make_fastdiv(d));
 }
 
 extern "C" int tt_variant_info(int variant_id, int32_t out[9])

@@ -28,23 +28,22 @@ template <int DT, int FAM> __global__ void __launch_bounds__(256) direct_kernel(
     float acc = 0.0f;
     int n;
     if constexpr (FAM == FAM_CONV) {
-        // idx walks the NCHW output: (img, n, p, q)
-        const int hw = g.Ho * g.Wo;
-        const int q = (int)(idx % g.Wo), p = (int)((idx / g.Wo) % g.Ho);
-        n = (int)((idx / hw) % g.N);
-        const int img = (int)(idx / ((int64_t)hw * g.N));
-        for (int c = 0; c < g.C; ++c)
-            for (int r = 0; r < g.R; ++r) {
-                const int ih = p * g.stride_h + r - g.pad_h;
-                if (ih < 0 || ih >= g.H) continue;
-                for (int s = 0; s < g.S; ++s) {
-                    const int iw = q * g.stride_w + s - g.pad_w;
-                    if (iw < 0 || iw >= g.W) continue;
-                    const float xv = load_as_float<DT>(a, (((int64_t)img * g.C + c) * g.H + ih) * g.W + iw);
-                    const float wv = load_as_float<DT>(b, (((int64_t)n * g.C + c) * g.R + r) * g.S + s);
-                    acc = fmaf(xv, wv, acc);
-                }
+        // idx walks the NHWC output: (img, p, q, n); activations NHWC, filters KRSC
+        n = (int)(idx % g.N);
+        const int64_t pix = idx / g.N;
+        const int q = (int)(pix % g.Wo), p = (int)((pix / g.Wo) % g.Ho);
+        const int img = (int)(pix / ((int64_t)g.Ho * g.Wo));
+        for (int r = 0; r < g.R; ++r) {
+            const int ih = p * g.stride_h + r - g.pad_h;
+            if (ih < 0 || ih >= g.H) continue;
+            for (int s = 0; s < g.S; ++s) {
+                const int iw = q * g.stride_w + s - g.pad_w;
+                if (iw < 0 || iw >= g.W) continue;
+                const E *xp = a + (((int64_t)img * g.H + ih) * g.W + iw) * g.C;
+                const E *wp = b + (((int64_t)n * g.R + r) * g.S + s) * g.C;
+                for (int c = 0; c < g.C; ++c) acc = fmaf(load_as_float<DT>(xp, c), load_as_float<DT>(wp, c), acc);
             }
+        }
     } else {
         n = (int)(idx % g.N);
         const int m = (int)((idx / g.N) % g.M);
@@ -63,14 +62,14 @@ template <int DT, int FAM> __global__ void __launch_bounds__(256) direct_kernel(
 }
 
 // ---- split-K: sum the partial tiles in split order, then the fused epilogue -----------------------
-template <int DT, bool CONV> __global__ void __launch_bounds__(256) splitk_reduce_kernel(const ContractArgs g)
+template <int DT> __global__ void __launch_bounds__(256) splitk_reduce_kernel(const ContractArgs g)
 {
     const int64_t total = (int64_t)g.batch * g.M * g.N;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     float acc = 0.0f;
     for (int z = 0; z < g.map.eff_split_k; ++z) acc += g.ws[(int64_t)z * total + idx];
-    const int n = CONV ? (int)((idx / ((int64_t)g.Ho * g.Wo)) % g.N) : (int)(idx % g.N);
+    const int n = (int)(idx % g.N);
     if (g.has_bias) acc += load_as_float<DT>(g.bias, n);
     if (g.has_res) acc += load_as_float<DT>(g.res, idx);
     store_from_float<DT>(g.out, idx, apply_act(acc, g.act));
@@ -125,42 +124,46 @@ template <int DT> __global__ void gemv_kernel(const ContractArgs g, int tile_m, 
         }
 }
 
-// ---- depthwise 3x3: (planes, rows, cols) tile per workgroup, WM x WN outputs per thread -----------
-// Threads are laid out cols fastest, then rows, then planes, so a wave reads and writes whole row
-// segments.  With two stages the input patch of the tile is first copied to LDS.
+// ---- depthwise 3x3 over NHWC: (rows, cols, planes) tile per workgroup, WM x WN outputs per thread ---
+// A plane is one (image, channel) pair, numbered image * C + channel.  Threads are laid out planes
+// fastest, then cols, then rows, so the lanes of a wave read and write neighbouring channels of one
+// pixel.  With two stages the input patch of the tile is first copied to LDS (planes fastest too).
 template <int WM, int WN> __global__ void dwconv3x3_kernel(const DwArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float *patch = reinterpret_cast<float *>(smem_raw);
     const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
-    const int tcols = g.map.tile_n / WN, trows = g.map.tile_m / WM;
+    const int tk = g.map.tile_k;
+    const int tcols = g.map.tile_n / WN;
     const int tid = threadIdx.x;
-    const int tx = tid % tcols, ty = (tid / tcols) % trows, tp = tid / (tcols * trows);
+    const int tp = tid % tk, tx = (tid / tk) % tcols, ty = tid / (tk * tcols);
     const int plane = tc.k0 + tp;
     const int p0 = tc.m0 + ty * WM, q0 = tc.n0 + tx * WN;
     const int prow = (g.map.tile_m - 1) * g.stride_h + 3, pcol = (g.map.tile_n - 1) * g.stride_w + 3;
     const int ih_org = tc.m0 * g.stride_h - g.pad_h, iw_org = tc.n0 * g.stride_w - g.pad_w;
     if (g.stages == 2) {
-        const int per_plane = prow * pcol, total = per_plane * g.map.tile_k;
+        const int total = prow * pcol * tk;
         for (int e = tid; e < total; e += blockDim.x) {
-            const int pl = e / per_plane, rem = e - pl * per_plane;
-            const int rr = rem / pcol, cc = rem - rr * pcol;
+            const int pl = e % tk, cell = e / tk;
+            const int rr = cell / pcol, cc = cell - rr * pcol;
             const int ih = ih_org + rr, iw = iw_org + cc;
             float v = 0.0f;
-            if (pl < tc.k_ext && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
-                v = g.x[((int64_t)(tc.k0 + pl) * g.H + ih) * g.W + iw];
+            if (pl < tc.k_ext && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
+                const int pn = (tc.k0 + pl) / g.C, pc = (tc.k0 + pl) - pn * g.C;
+                v = g.x[(((int64_t)pn * g.H + ih) * g.W + iw) * g.C + pc];
+            }
             patch[e] = v;
         }
         __syncthreads();
     }
     if (tp >= tc.k_ext) return;
-    const int ch = plane % g.C;
+    const int img = plane / g.C, ch = plane - img * g.C;
     float wgt[9];
 #pragma unroll
-    for (int i = 0; i < 9; ++i) wgt[i] = g.w[ch * 9 + i];
+    for (int i = 0; i < 9; ++i) wgt[i] = g.w[i * g.C + ch];
     const float bias = g.bias ? g.bias[ch] : 0.0f;
-    const float *xp = g.x + (int64_t)plane * g.H * g.W;
-    float *yp = g.y + (int64_t)plane * g.Ho * g.Wo;
+    const float *xp = g.x + (int64_t)img * g.H * g.W * g.C + ch;
+    float *yp = g.y + (int64_t)img * g.Ho * g.Wo * g.C + ch;
     auto body = [&](int i) {
         const int p = p0 + i;
         if (p >= g.Ho || p >= tc.m0 + tc.m_ext) return;
@@ -177,27 +180,18 @@ template <int WM, int WN> __global__ void dwconv3x3_kernel(const DwArgs g)
                     const int iw = (q0 + j) * g.stride_w + s - g.pad_w;
                     float v = 0.0f;
                     if (g.stages == 2) {
-                        v = patch[(tp * prow + (ih - ih_org)) * pcol + (iw - iw_org)];
+                        v = patch[((ih - ih_org) * pcol + (iw - iw_org)) * tk + tp];
                     } else if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
-                        v = xp[(int64_t)ih * g.W + iw];
+                        v = xp[((int64_t)ih * g.W + iw) * g.C];
                     }
                     out[j] = fmaf(v, wgt[r * 3 + s], out[j]);
                 }
             }
         }
         const int qlim = min(g.Wo, tc.n0 + tc.n_ext);
-        if (WN == 4 && g.eff_vec == 4 && q0 + 3 < qlim) {
-            float4 o;
-            o.x = fminf(fmaxf(out[0], 0.0f), 6.0f);
-            o.y = fminf(fmaxf(out[1 % WN], 0.0f), 6.0f);
-            o.z = fminf(fmaxf(out[2 % WN], 0.0f), 6.0f);
-            o.w = fminf(fmaxf(out[3 % WN], 0.0f), 6.0f);
-            *reinterpret_cast<float4 *>(yp + (int64_t)p * g.Wo + q0) = o;
-        } else {
 #pragma unroll
-            for (int j = 0; j < WN; ++j)
-                if (q0 + j < qlim) yp[(int64_t)p * g.Wo + q0 + j] = fminf(fmaxf(out[j], 0.0f), 6.0f);
-        }
+        for (int j = 0; j < WN; ++j)
+            if (q0 + j < qlim) yp[((int64_t)p * g.Wo + q0 + j) * g.C] = fminf(fmaxf(out[j], 0.0f), 6.0f);
     };
     if (g.unroll >= WM) {
 #pragma unroll
@@ -210,12 +204,14 @@ template <int WM, int WN> __global__ void dwconv3x3_kernel(const DwArgs g)
 
 __global__ void __launch_bounds__(256) dw_direct_kernel(const DwArgs g)
 {
+    // idx walks the NHWC output: (image, p, q, channel)
     const int64_t total = (int64_t)g.planes * g.Ho * g.Wo;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
-    const int q = (int)(idx % g.Wo), p = (int)((idx / g.Wo) % g.Ho);
-    const int plane = (int)(idx / ((int64_t)g.Ho * g.Wo));
-    const int ch = plane % g.C;
+    const int ch = (int)(idx % g.C);
+    const int64_t pix = idx / g.C;
+    const int q = (int)(pix % g.Wo), p = (int)((pix / g.Wo) % g.Ho);
+    const int img = (int)(pix / ((int64_t)g.Ho * g.Wo));
     float acc = 0.0f;
     for (int r = 0; r < 3; ++r) {
         const int ih = p * g.stride_h + r - g.pad_h;
@@ -223,7 +219,7 @@ __global__ void __launch_bounds__(256) dw_direct_kernel(const DwArgs g)
         for (int s = 0; s < 3; ++s) {
             const int iw = q * g.stride_w + s - g.pad_w;
             if (iw < 0 || iw >= g.W) continue;
-            acc = fmaf(g.x[((int64_t)plane * g.H + ih) * g.W + iw], g.w[ch * 9 + r * 3 + s], acc);
+            acc = fmaf(g.x[(((int64_t)img * g.H + ih) * g.W + iw) * g.C + ch], g.w[(r * 3 + s) * g.C + ch], acc);
         }
     }
     if (g.bias) acc += g.bias[ch];
@@ -270,17 +266,11 @@ int launch_splitk_reduce(const ContractArgs &args, int family, void *stream)
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t total = (int64_t)args.batch * args.M * args.N;
     const int grid = (int)((total + 255) / 256);
-    if (family == FAM_CONV) {
-        if (args.dtype == TT_F32)
-            hipLaunchKernelGGL((splitk_reduce_kernel<TT_F32, true>), dim3(grid), dim3(256), 0, s, args);
-        else
-            hipLaunchKernelGGL((splitk_reduce_kernel<TT_BF16, true>), dim3(grid), dim3(256), 0, s, args);
-    } else {
-        if (args.dtype == TT_F32)
-            hipLaunchKernelGGL((splitk_reduce_kernel<TT_F32, false>), dim3(grid), dim3(256), 0, s, args);
-        else
-            hipLaunchKernelGGL((splitk_reduce_kernel<TT_BF16, false>), dim3(grid), dim3(256), 0, s, args);
-    }
+    (void)family; // every family writes a row-major [M][N] output
+    if (args.dtype == TT_F32)
+        hipLaunchKernelGGL((splitk_reduce_kernel<TT_F32>), dim3(grid), dim3(256), 0, s, args);
+    else
+        hipLaunchKernelGGL((splitk_reduce_kernel<TT_BF16>), dim3(grid), dim3(256), 0, s, args);
     return launched();
 }
 

@@ -109,10 +109,27 @@ inline TileMap tile_map_of(const tt_plan &pl)
     return m;
 }
 
+// Exact n / d for 0 <= n < 2^31 and 1 <= d < 2^31 by one widening multiply:
+// magic = ceil(2^(31+shift) / d) with shift = ceil(log2 d) fits 32 bits, and the
+// error n * (magic * d - 2^(31+shift)) / (d * 2^(31+shift)) stays below 1/d.
+struct FastDiv {
+    uint32_t magic, shift;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.shift = 0;
+    while ((1ull << f.shift) < d) ++f.shift;
+    const uint64_t pw = 1ull << (31 + f.shift);
+    f.magic = (uint32_t)((pw + d - 1) / d);
+    return f;
+}
+TT_HD uint32_t fast_div(uint32_t n, const FastDiv &f) { return (uint32_t)((((uint64_t)n * f.magic) >> 31) >> f.shift); }
+
 // Operand families of the matrix-core contraction kernel.
 enum Family {
-    FAM_CONV = 0,    // A = NCHW activations gathered as an implicit GEMM, B = KCRS filters ([N][K])
-    FAM_GEMM_TN = 1, // A = [M][K], B = [N][K] (dense; batch matmul with trans_b = 1)
+    FAM_CONV = 0,    // A = NHWC activations gathered as an implicit GEMM, B = KRSC filters ([N][K])
+    FAM_GEMM_TN = 1, // A = [M][K], B = [N][K] (dense; batch matmul with trans_b = 1; unit-stride 1x1 conv)
     FAM_GEMM_NN = 2  // A = [M][K], B = [K][N] (batch matmul with trans_b = 0)
 };
 
@@ -123,8 +140,13 @@ struct ContractArgs {
     float *ws;
     TileMap map;
     int32_t batch, M, N, K;
-    // convolution geometry (FAM_CONV)
+    // convolution geometry (FAM_CONV).  The reduction index is k = r * runp + j: filter row r and
+    // position j inside the run of S * C elements that one filter row covers contiguously in an
+    // NHWC image row (and in a KRSC filter); runp is the run rounded up to whole 16-byte items.
     int32_t C, H, W, R, S, stride_h, stride_w, pad_h, pad_w, Ho, Wo;
+    int32_t run, runp;
+    FastDiv div_hw, div_wo; // output pixel index -> (image, row, column)
+    uint32_t a_bytes, b_bytes; // sizes of the activation and filter tensors (bounds of the gathering loads)
     int32_t eff_vec_a, eff_vec_b, eff_vec_c, stages, unroll, act, has_bias, has_res, dtype;
 };
 
@@ -133,12 +155,12 @@ struct DwArgs {
     float *y;
     TileMap map;
     int32_t planes, C, H, W, Ho, Wo, stride_h, stride_w, pad_h, pad_w;
-    int32_t wave_m, wave_n, eff_vec, stages, unroll;
+    int32_t wave_m, wave_n, stages, unroll;
 };
 
 struct Variant {
     int32_t dtype, family, tile_m, tile_n, tile_k, wave_m, wave_n, mfma;
-    int32_t amode; // conv family: bytes per activation load (16, 4 or the element size); 0 otherwise
+    int32_t amode; // conv family: bytes per gathered load (16 or the element size); 0 otherwise
     int (*launch)(const ContractArgs &args, int grid, int lds_bytes, void *stream);
 };
 

@@ -13,10 +13,30 @@ def to_device(arr: np.ndarray, dtype: int):
     return t.to(torch.bfloat16) if dtype == wl.BF16 else t
 
 
+def to_library_layout(kernel: wl.Kernel, name: str, arr: np.ndarray) -> np.ndarray:
+    """Permute a tensor from the operator definition's index order to the library's storage order.
+
+    The workloads (and the paper's listings) index convolution tensors as
+    [n,c,h,w] / [k,c,r,s]; the library stores them channels-last, [n,h,w,c] /
+    [k,r,s,c] ([r,s,c] for depthwise filters).  A pure permutation: no value changes.
+    """
+    if not kernel.is_conv() or name == "bias":
+        return arr
+    if name == "w" and kernel.cls == wl.CLS_DWCONV_BIAS_RELU6:
+        return np.ascontiguousarray(arr[:, 0].transpose(1, 2, 0))
+    return np.ascontiguousarray(arr.transpose(0, 2, 3, 1))
+
+
+def output_in_definition_order(kernel: wl.Kernel, y):
+    """The library's output tensor viewed in the definition's index order ([n,k,Ho,Wo] for conv)."""
+    return y.permute(0, 3, 1, 2) if kernel.is_conv() else y
+
+
 def output_shape(kernel: wl.Kernel):
+    """Shape of the output as the library stores it."""
     s = kernel.shape
     if kernel.is_conv():
-        return (s.n, s.k, s.ho, s.wo)
+        return (s.n, s.ho, s.wo, s.k)
     if kernel.cls == wl.CLS_BATCH_MATMUL:
         return (s.batch, s.m, s.n)
     return (s.m, s.n)
@@ -34,7 +54,7 @@ def device_kernel(kernel: wl.Kernel, seed: int, inputs: dict | None = None, max_
     import torch
     host = inputs if inputs is not None else wl.make_inputs(kernel, seed)
     dt = kernel.shape.dtype
-    tensors = {k: to_device(v, dt) for k, v in host.items()}
+    tensors = {k: to_device(to_library_layout(kernel, k, v), dt) for k, v in host.items()}
     out_key = "c" if kernel.cls == wl.CLS_BATCH_MATMUL else "y"
     tensors[out_key] = torch.zeros(output_shape(kernel), dtype=api.torch_dtype(dt), device="cuda")
     return api.DeviceKernel(kernel.cls, kernel.shape, tensors, kernel.use_count, kernel.name,

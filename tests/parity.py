@@ -37,13 +37,14 @@ def assert_close(got: np.ndarray, ref: np.ndarray, dtype: int, what=""):
     assert err.max() <= tol * max(np.abs(ref).max(), 1e-30), (what, float(err.max()))
 
 
-def run_gpu(dk: api.DeviceKernel, sched=None) -> np.ndarray:
+def run_gpu(kernel: wl.Kernel, dk: api.DeviceKernel, sched=None) -> np.ndarray:
+    """Run once and return the output in the definition's index order ([n,k,Ho,Wo] for conv)."""
     import torch
     dk.output().fill_(float("nan"))
     rc = dk.run(sched)
     torch.cuda.synchronize()
     assert rc == api.TT_OK, (api.status_name(rc), sched)
-    return dk.output().float().cpu().numpy()
+    return harness.output_in_definition_order(kernel, dk.output()).float().cpu().numpy()
 
 
 def check_kernel(kernel: wl.Kernel, scheds, seed=1234, ref=None):
@@ -70,7 +71,7 @@ def check_kernel(kernel: wl.Kernel, scheds, seed=1234, ref=None):
                 assert dk.run(s) == api.TT_ERR_UNSUPPORTED, (kernel.name, s)
                 outs.append(None)
                 continue
-        got = run_gpu(dk, s)
+        got = run_gpu(kernel, dk, s)
         assert_close(got, ref, kernel.shape.dtype, f"{kernel.name} {s}")
         outs.append(got)
     return ref, outs

@@ -95,7 +95,7 @@ def test_cfg5_full_size_sampled(index):
         rc = dk.run(rec)
         torch.cuda.synchronize()
         assert rc == api.TT_OK, (kernel.name, rec, api.status_name(rc))
-        y = dk.output()
+        y = harness.output_in_definition_order(kernel, dk.output())
         assert bool(torch.isfinite(y).all()), (kernel.name, rec, "unwritten or non-finite outputs")
         if act == wl.ACT_RELU:
             assert float(y.min()) >= 0.0

@@ -61,7 +61,7 @@ def test_cfg1_conv_under_default_and_donor_tiles(api, P):
     ref, outs = P.check_kernel(k, scheds)
     assert ref.min() >= 0.0
     # same (tile_k, split_k, block) => same summation order => identical bits, whatever the tile shape
-    a = P.run_gpu(__import__("paper_2201_05587_amd.harness", fromlist=["x"]).device_kernel(k, 1234),
+    a = P.run_gpu(k, __import__("paper_2201_05587_amd.harness", fromlist=["x"]).device_kernel(k, 1234),
                   mfma(api, E, 64, 64, 32, 32, 32, 32))
     np.testing.assert_array_equal(a, outs[2])
 

@@ -27,7 +27,7 @@ def plan_equal(cplan: api.tt_plan, oplan: dict):
 def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "tt.h")) as f:
         text = f.read()
-    declared = set(re.findall(r"^(?:int|const char \*)\s*(tt_\w+)\(", text, flags=re.M))
+    declared = set(re.findall(r"^(?:int|int64_t|const char \*)\s*(tt_\w+)\(", text, flags=re.M))
     assert declared == set(api.EXPORTS), declared ^ set(api.EXPORTS)
     for name in declared:
         assert hasattr(api.lib, name)
@@ -143,3 +143,21 @@ def test_schedule_space_is_well_formed_and_contains_the_default_tiles():
         assert plan.status == api.TT_OK
         if plan.sketch == api.TT_SK_MFMA:
             assert plan.variant_id >= 0, (k.name, rec)
+
+
+def test_division_by_multiplication_is_exact():
+    """The kernels turn a pixel index into (image, row, column) with a multiply; it must equal n // d."""
+    import random
+    from paper_2201_05587_amd import api
+    rnd = random.Random(5)
+    top = 2 ** 31 - 1
+    ds = list(range(1, 300)) + [7 * 7, 14 * 14, 56 * 56, 112 * 112, 2 ** 16, 2 ** 16 + 1, 2 ** 30, 2 ** 30 + 1, top]
+    ds += [rnd.randrange(1, top) for _ in range(300)]
+    for d in ds:
+        ns = [0, 1, d - 1, d, d + 1, top, top - 1, (top // d) * d, max((top // d) * d - 1, 0)]
+        ns += [rnd.randrange(0, top) for _ in range(40)] + [k * d - 1 for k in range(1, 40) if k * d - 1 <= top]
+        for n in ns:
+            if n > top:
+                continue
+            assert api.lib.tt_debug_fast_div(n, d) == n // d, (n, d)
+    assert api.lib.tt_debug_fast_div(5, 0) == -1 and api.lib.tt_debug_fast_div(2 ** 31, 3) == -1

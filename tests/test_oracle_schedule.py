@@ -141,16 +141,19 @@ def test_split_k_and_resource_validity():
 
 
 def test_vector_width_and_unroll_are_reformulated_not_rejected():
-    stem = S.conv_shape(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)  # K = 147 (odd), stride 2
+    stem = S.conv_shape(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)  # 3 channels: no vector fits a pixel
     p = S.apply(S.record(E, vec=4, unroll=512), E, stem)
     assert p["status"] == S.OK and (p["eff_vec_a"], p["eff_vec_b"], p["eff_vec_c"]) == (1, 1, 4)
+    # the reduction is 7 filter rows x (7 * 3 = 21 elements rounded up to 24, six 16-byte fp32 items)
+    assert p["K"] == 7 * 24 and S.apply(S.record(E), E, cfg1_shape())["K"] == 64 * 3 * 3
     assert p["eff_unroll"] == 1  # tile_k 16 with the 16-wide fp32 block is a single step
     p = S.apply(S.record(E, vec=4, tile_k=32, mfma=32, unroll=512), E, cfg1_shape())
     assert (p["eff_vec_a"], p["eff_vec_b"], p["eff_vec_c"], p["eff_unroll"]) == (4, 4, 4, 4)
-    s14 = S.conv_shape(1, 256, 14, 14, 256, 3, 3, 1, 1, 1, 1)
-    assert S.apply(S.record(E, vec=4), E, s14)["eff_vec_a"] == 2    # rows of 14 outputs
-    pw = S.conv_shape(1, 96, 14, 14, 576, 1, 1, dtype=S.DT_BF16)
-    assert S.apply(S.record(E, vec=8, tile_k=32), E, pw)["eff_vec_a"] == 4   # 196 = 4 * 49
+    c6 = S.conv_shape(1, 6, 14, 14, 256, 3, 3, 1, 1, 1, 1)
+    assert S.apply(S.record(E, vec=4), E, c6)["eff_vec_a"] == 2    # pixels of 6 channels
+    pw = S.conv_shape(1, 36, 14, 14, 576, 1, 1, dtype=S.DT_BF16)
+    p = S.apply(S.record(E, vec=8, tile_k=32), E, pw)
+    assert (p["eff_vec_a"], p["eff_vec_c"], p["K"]) == (4, 8, 40)   # 36 = 4 * 9; 36 rounded up to 8-element items
 
 
 def test_malformed_records_and_shapes_are_argument_errors():
