@@ -130,7 +130,9 @@ typedef struct tt_gemm_shape {
  *                the reduction (Parallel on a reduction axis); order = workgroup raster (Reorder +
  *                Fuse of the two parallel axes, see tt_plan_tile); vec = elements per global access
  *                (Vectorize); unroll = depth to which the per-tile K-step loop is unrolled (Unroll);
- *                stages = LDS buffers, 1 or 2 (cache buffer + ComputeAt).
+ *                stages = LDS buffers (cache buffer + ComputeAt): 1 or 2 with register-staged loads,
+ *                3 or 4 = ring filled by asynchronous global-to-LDS loads (reformulated to 2 where
+ *                the ring does not apply: partial 16-byte items, [K][N] operands, odd tile/thread ratios).
  *   TT_SK_GEMV   tile_m (= wave_m) rows and tile_n outputs per workgroup, wave_n outputs per wave,
  *                tile_k = K elements a wave consumes per step (64 lanes x 1/2/4/8), mfma = 0.
  *   TT_SK_DWCONV tile_m x tile_n output rows x cols and tile_k planes per workgroup, wave_m x wave_n
@@ -147,7 +149,7 @@ typedef struct tt_schedule {
     int32_t order;  /* 0 M-tiles fastest, 1 N-tiles fastest, 2 bands of 8 M-tiles; +3 = XCD-contiguous */
     int32_t vec;    /* 1, 2, 4 or 8 */
     int32_t unroll; /* >= 1 */
-    int32_t stages; /* 1 or 2 */
+    int32_t stages; /* 1..4 (matrix-core sketch), 1 or 2 (others) */
     /* provenance (ignored by tt_schedule_apply): */
     int32_t id;              /* caller's identifier of the record                     */
     int32_t donor_shape[12]; /* the shape the record was tuned on (struct as int32[]) */
@@ -321,12 +323,13 @@ int tt_run_kernels(const tt_kernel_desc *kernels, const tt_schedule *const *sche
 int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out, int cap);
 
 /*
- * Template arguments of a compiled matrix-core kernel variant (tt_plan.variant_id): out[9] =
+ * Template arguments of a compiled matrix-core kernel variant (tt_plan.variant_id): out[10] =
  * {dtype, family (0 conv, 1 GEMM with [N][K] B, 2 GEMM with [K][N] B), tile_m, tile_n, tile_k, wave_m,
- * wave_n, mfma, bytes per activation load (conv family; 0 otherwise)} - the order they appear in the
- * kernel's symbol name.  TT_ERR_BAD_ARG for an id outside the table.
+ * wave_n, mfma, bytes per gathered load (conv family; 0 otherwise), pipeline (0 register-staged,
+ * symbol contract_kernel with the first nine arguments; 1 asynchronous ring, symbol
+ * contract_async_kernel with the first eight)}.  TT_ERR_BAD_ARG for an id outside the table.
  */
-int tt_variant_info(int variant_id, int32_t out[9]);
+int tt_variant_info(int variant_id, int32_t out[10]);
 
 /* Pure selection step of the sweep on given times (host only; the rule tt_transfer_sweep uses). */
 int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t *pool_cls, int np, const double *pair_us,

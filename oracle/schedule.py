@@ -260,7 +260,7 @@ def record_is_well_formed(rec: dict) -> bool:
         return False
     if rec["split_k"] < 1 or rec["order"] < 0 or rec["order"] >= 6 or rec["vec"] not in (1, 2, 4, 8):
         return False
-    if rec["unroll"] < 1 or rec["stages"] not in (1, 2):
+    if rec["unroll"] < 1 or rec["stages"] < 1 or rec["stages"] > (4 if sk == SK_MFMA else 2):
         return False
     tm, tn, tk, wm, wn, mf = (rec[f] for f in ("tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfma"))
     if sk == SK_MFMA:
@@ -389,17 +389,34 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_NOT_DIVISIBLE)
     k_iters = ceil_div(k_tiles, rec["split_k"])
     eff_split_k = ceil_div(k_tiles, k_iters)  # no empty split
-    lds = rec["stages"] * staged_tile_bytes(cls, shape, rec)
-    if lds > LDS_BUDGET:
-        return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
     if cls in CONV_CLASSES:
         # vectors run along the channel axis of both operands and along the output channels
         eva = evb = pow2_dividing(vmax, shape["c"])
         evc = pow2_dividing(vmax, N)
+        whole_items = eva * elem == 16
+        in_range = True  # the operator refuses larger tensors for every matrix-core record
     else:
         eva = pow2_dividing(vmax, K)
         evb = pow2_dividing(vmax, K) if shape["trans_b"] else pow2_dividing(vmax, N)
         evc = pow2_dividing(vmax, N)
+        whole_items = bool(shape["trans_b"]) and eva * elem == 16
+        in_range = M * K * elem < 2 ** 31 and N * K * elem < 2 ** 31
+    # Three or four stages ask for the asynchronous ring of unpadded LDS buffers; where it does not
+    # apply the record is reformulated to two stages.
+    block = 64 * (tm // rec["wave_m"]) * (tn // rec["wave_n"])
+    chunks = tk * elem // 16
+    ring_fits = (whole_items and in_range and (tm * chunks) % block == 0 and (tn * chunks) % block == 0
+                 and (block // 16) % chunks == 0)
+    stages = rec["stages"]
+    if stages >= 3 and not ring_fits:
+        stages = 2
+    plan["stages"] = stages
+    if stages >= 3:
+        lds = stages * (tm + tn) * tk * elem
+    else:
+        lds = stages * staged_tile_bytes(cls, shape, rec)
+    if lds > LDS_BUDGET:
+        return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
     waves = (tm // rec["wave_m"]) * (tn // rec["wave_n"])
     slabs = batch * eff_split_k
     grid = tiles_m * tiles_n * slabs

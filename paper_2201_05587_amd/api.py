@@ -121,7 +121,7 @@ def _load():
     lib.tt_run_kernels.argtypes = [POINTER(tt_kernel_desc), POINTER(POINTER(tt_schedule)), ctypes.c_int, ctypes.c_int,
                                    c_void_p]
     lib.tt_schedule_space.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(tt_schedule), ctypes.c_int]
-    lib.tt_variant_info.argtypes = [ctypes.c_int, POINTER(c_int32 * 9)]
+    lib.tt_variant_info.argtypes = [ctypes.c_int, POINTER(c_int32 * 10)]
     lib.tt_sweep_select.argtypes = [POINTER(c_int32), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
                                     POINTER(c_double), ctypes.c_int, POINTER(tt_sweep_row)]
     for name in EXPORTS:
@@ -408,8 +408,10 @@ class KernelList:
 def variant_name(plan: tt_plan) -> str:
     """Name of the kernel a plan launches, spelled like the demangled symbol rocprofv3 reports."""
     if plan.sketch == TT_SK_MFMA:
-        info = (c_int32 * 9)()
+        info = (c_int32 * 10)()
         _check(lib.tt_variant_info(plan.variant_id, byref(info)), "tt_variant_info")
-        return "tt::contract_kernel<" + ", ".join(str(v) for v in info) + ">"
+        if info[9]:
+            return "tt::contract_async_kernel<" + ", ".join(str(v) for v in info[:8]) + ">"
+        return "tt::contract_kernel<" + ", ".join(str(v) for v in info[:9]) + ">"
     return {TT_SK_GEMV: "tt::gemv_kernel", TT_SK_DWCONV: f"tt::dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}>",
             TT_SK_DIRECT: "tt::direct_kernel"}[plan.sketch]

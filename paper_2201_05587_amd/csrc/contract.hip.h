@@ -414,6 +414,113 @@ template <int DT, int MF, int LEN> __device__ __forceinline__ u32x4 kmajor_fragm
 }
 
 
+// ---- epilogue ---------------------------------------------------------------------------------------------------
+// The accumulators hold, per lane, 4 consecutive ROWS of one column, while memory is contiguous
+// along COLUMNS.  Each wave therefore passes its tile through a private LDS region, one band of
+// MF rows at a time, and reads it back so that a lane owns 8 consecutive columns of one row:
+// bias, residual, activation and down-conversion then work on 16-byte vectors (or on the widest
+// sub-vectors the output's row length allows), and stores are fully coalesced.  With split-K
+// the raw partial sums go to the workspace in the same pattern.
+template <int DT, int TM, int WM, int WN, int MF, typename Acc>
+__device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
+                                           unsigned char *smem, int wave, int lane)
+{
+    constexpr int NWR = TM / WM, NI = WM / MF, NJ = WN / MF, ACC = MF * MF / 64;
+    const int wr = wave % NWR, wc = wave / NWR;
+    const int lane_r = lane % MF, lane_g = lane / MF;
+    const int bidx = tc.hi;
+    {
+        constexpr int ESTRIDE = WN + (MF == 32 ? 8 : 4);      // floats per staged row (bank-conflict padding)
+        constexpr int CG = WN / 8;                            // 8-column groups per row
+        constexpr int ROWS_PER_PASS = 64 / CG;                // rows the 64 lanes cover at once
+        constexpr int PASSES = (MF + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
+        float *stage = reinterpret_cast<float *>(smem) + wave * (MF * ESTRIDE);
+        const bool partial = g.map.eff_split_k > 1;
+        const int64_t mn = (int64_t)g.M * g.N;
+        float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
+        const int vc = g.eff_vec_c; // consecutive outputs of a row that are all inside or all outside the matrix
+        const int cg = lane % CG, row_in_pass = lane / CG;
+        const int c0 = wc * WN + cg * 8; // first of this lane's 8 columns inside the workgroup tile
+
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            __syncthreads(); // the band before this one has been read (and the K loop is over)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int v = 0; v < ACC; ++v) {
+                    const int row_l = MF == 32 ? (v / 4) * 8 + lane_g * 4 + (v % 4) : lane_g * 4 + v;
+                    stage[row_l * ESTRIDE + j * MF + lane_r] = acc[i][j][v];
+                }
+            __syncthreads();
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int row_l = ps * ROWS_PER_PASS + row_in_pass;
+                if (ROWS_PER_PASS * PASSES > MF && row_l >= MF) continue;
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
+                float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                const int m = tc.m0 + wr * WM + i * MF + row_l;
+                if (m >= g.M) continue;
+                const int first = tc.n0 + c0;
+                // groups of vc consecutive columns
+                for (int e0 = 0; e0 < 8; e0 += vc) {
+                    const int n = first + e0;
+                    if (n >= g.N) break;
+                    const int64_t idx = (int64_t)bidx * mn + (int64_t)m * g.N + n;
+                    if (partial) {
+                        if (vc == 8) {
+                            *reinterpret_cast<f32x4 *>(ws + idx) = lo;
+                            *reinterpret_cast<f32x4 *>(ws + idx + 4) = hi;
+                        } else if (vc == 4) {
+                            *reinterpret_cast<f32x4 *>(ws + idx) = e0 == 0 ? lo : hi;
+                        } else {
+                            for (int e = 0; e < vc; ++e) ws[idx + e] = val[e0 + e];
+                        }
+                        continue;
+                    }
+                    if (vc == 8 && DT == TT_BF16) {
+                        u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
+                        if (g.has_res) resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
+                        if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
+                        u32x4 outv;
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
+                            float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) +
+                                      __uint_as_float(resv[h] & 0xffff0000u);
+                            outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
+                                      ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
+                        }
+                        *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
+                    } else if (vc >= 4 && DT == TT_F32) {
+#pragma unroll
+                        for (int q4 = 0; q4 < 2; ++q4) {
+                            if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
+                            f32x4 r = q4 == 0 ? lo : hi;
+                            const int64_t at = idx + (q4 * 4 - e0);
+                            f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
+                            if (g.has_bias)
+                                add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
+                            if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
+                            *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
+                        }
+                    } else {
+                        for (int e = 0; e < vc; ++e) {
+                            float a = val[e0 + e];
+                            if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
+                            if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
+                            store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
 // LDS bytes of one pipeline stage: the A tile followed by the B tile.
 template <int DT, int FAM, int TM, int TN, int TK, int MF> struct StageLayout {
     using E = typename ElemOf<DT>::type;
@@ -561,103 +668,256 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
         if (two_stage) cur ^= 1;
     }
 
-    // ---- epilogue ------------------------------------------------------------------------------------------
-    // The accumulators hold, per lane, 4 consecutive ROWS of one column, while memory is contiguous
-    // along COLUMNS.  Each wave therefore passes its tile through a private LDS region, one band of
-    // MF rows at a time, and reads it back so that a lane owns 8 consecutive columns of one row:
-    // bias, residual, activation and down-conversion then work on 16-byte vectors (or on the widest
-    // sub-vectors the output's row length allows), and stores are fully coalesced.  With split-K
-    // the raw partial sums go to the workspace in the same pattern.
-    {
-        constexpr int ESTRIDE = WN + (MF == 32 ? 8 : 4);      // floats per staged row (bank-conflict padding)
-        constexpr int CG = WN / 8;                            // 8-column groups per row
-        constexpr int ROWS_PER_PASS = 64 / CG;                // rows the 64 lanes cover at once
-        constexpr int PASSES = (MF + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
-        float *stage = reinterpret_cast<float *>(smem) + wave * (MF * ESTRIDE);
-        const bool partial = g.map.eff_split_k > 1;
-        const int64_t mn = (int64_t)g.M * g.N;
-        float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
-        const int vc = g.eff_vec_c; // consecutive outputs of a row that are all inside or all outside the matrix
-        const int cg = lane % CG, row_in_pass = lane / CG;
-        const int c0 = wc * WN + cg * 8; // first of this lane's 8 columns inside the workgroup tile
+    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane);
+}
 
+// ---- asynchronous pipeline: global -> LDS without passing through registers --------------------------------------
+//
+// gfx950 buffer loads can deposit 16 bytes per lane straight into LDS (lane i of the wave writes
+// at M0 + 16 * i; an out-of-range offset deposits zeros).  Nothing of a slice lives in registers, so
+// several slices can be in flight: the K loop keeps a ring of `stages` LDS buffers, requests slice
+// t + stages - 1 while computing on slice t, and waits only for the oldest outstanding slice (the
+// vector-memory counter retires in order).  One barrier per slice both publishes the arrived
+// slice and frees the buffer that was computed on before it.
+//
+// A wave's 64 items land in 1 KB of consecutive LDS, so rows cannot be padded.  Bank conflicts of
+// the 16-byte fragment reads are avoided by a swizzle instead: the item holding K-chunk c of row r
+// is stored at chunk position c ^ swizzle(r), which spreads 16 consecutive rows of one chunk over
+// all banks.  The lane that fills LDS position p of a row simply fetches chunk p ^ swizzle(r).
+//
+// These loads are issued from inline assembly: the compiler would otherwise order every LDS read
+// after ALL outstanding loads.  They have no register results, and the kernel waits for them
+// explicitly (s_waitcnt vmcnt) before the barrier that precedes any read of their buffer.
+
+// chunk swizzle of row r for rows of CPR 16-byte chunks (CPR = 4, 8 or 16): depends on r mod 16 only
+template <int CPR> __device__ __forceinline__ int chunk_swizzle(int r) { return (r / (16 / CPR)) % CPR; }
+
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_offset, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(byte_offset), "s"(rsrc)
+                 : "memory");
+}
+
+template <int N> __device__ __forceinline__ void wait_loads_outstanding()
+{
+    static_assert(N >= 0 && N < 64, "vector-memory counter range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char *)p;
+}
+
+// Rows of a K-contiguous matrix [rows_total][K], K a multiple of the items' element count.
+template <int DT, int ROWS, int TK, int THREADS> struct AsyncRows {
+    static constexpr int CH = ElemOf<DT>::CH, ES = 16 / CH, CPR = TK / CH, TOTAL = ROWS * CPR, NL = TOTAL / THREADS;
+    static_assert(TOTAL % THREADS == 0 && (THREADS / 16) % CPR == 0, "tile does not fit the asynchronous loader");
+    struct State {
+        uint32_t at[NL]; // byte offset of this thread's chunk of the row at k = 0; out of range for rows past the matrix
+        int32_t kc;      // element offset of the chunk inside a slice
+    };
+    static __device__ __forceinline__ void init(State &st, int K, int row0, int rows_total, int tid)
+    {
+        const int first = tid / CPR, pos = tid % CPR;
+        st.kc = (pos ^ chunk_swizzle<CPR>(first)) * CH;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            __syncthreads(); // the band before this one has been read (and the K loop is over)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int v = 0; v < ACC; ++v) {
-                    const int row_l = MF == 32 ? (v / 4) * 8 + lane_g * 4 + (v % 4) : lane_g * 4 + v;
-                    stage[row_l * ESTRIDE + j * MF + lane_r] = acc[i][j][v];
-                }
-            __syncthreads();
-#pragma unroll
-            for (int ps = 0; ps < PASSES; ++ps) {
-                const int row_l = ps * ROWS_PER_PASS + row_in_pass;
-                if (ROWS_PER_PASS * PASSES > MF && row_l >= MF) continue;
-                const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8);
-                const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
-                float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                const int m = tc.m0 + wr * WM + i * MF + row_l;
-                if (m >= g.M) continue;
-                const int first = tc.n0 + c0;
-                // groups of vc consecutive columns
-                for (int e0 = 0; e0 < 8; e0 += vc) {
-                    const int n = first + e0;
-                    if (n >= g.N) break;
-                    const int64_t idx = (int64_t)bidx * mn + (int64_t)m * g.N + n;
-                    if (partial) {
-                        if (vc == 8) {
-                            *reinterpret_cast<f32x4 *>(ws + idx) = lo;
-                            *reinterpret_cast<f32x4 *>(ws + idx + 4) = hi;
-                        } else if (vc == 4) {
-                            *reinterpret_cast<f32x4 *>(ws + idx) = e0 == 0 ? lo : hi;
-                        } else {
-                            for (int e = 0; e < vc; ++e) ws[idx + e] = val[e0 + e];
-                        }
-                        continue;
-                    }
-                    if (vc == 8 && DT == TT_BF16) {
-                        u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
-                        if (g.has_res) resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
-                        if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
-                        u32x4 outv;
-#pragma unroll
-                        for (int h = 0; h < 4; ++h) {
-                            float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
-                            float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) +
-                                      __uint_as_float(resv[h] & 0xffff0000u);
-                            outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
-                                      ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
-                        }
-                        *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
-                    } else if (vc >= 4 && DT == TT_F32) {
-#pragma unroll
-                        for (int q4 = 0; q4 < 2; ++q4) {
-                            if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
-                            f32x4 r = q4 == 0 ? lo : hi;
-                            const int64_t at = idx + (q4 * 4 - e0);
-                            f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
-                            if (g.has_bias)
-                                add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
-                            if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
-                            *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
-                        }
-                    } else {
-                        for (int e = 0; e < vc; ++e) {
-                            float a = val[e0 + e];
-                            if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
-                            if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
-                            store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
-                        }
-                    }
-                }
-            }
+        for (int i = 0; i < NL; ++i) {
+            const int row = row0 + first + i * (THREADS / CPR);
+            st.at[i] = row < rows_total ? (uint32_t)(row * K + st.kc) * (uint32_t)ES : kOutOfRange;
         }
     }
+    static __device__ __forceinline__ void issue(const State &st, __amdgpu_buffer_rsrc_t rsrc, uint32_t lds_tile, int k0,
+                                                 int k_end, int wave)
+    {
+        const bool k_ok = k0 + st.kc < k_end;
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            load16_to_lds(rsrc, k_ok ? st.at[i] + (uint32_t)(k0 * ES) : kOutOfRange,
+                          lds_tile + (uint32_t)((i * THREADS + wave * 64) * 16));
+    }
+};
+
+// Implicit-GEMM rows of NHWC activations (see GatherLoader for the addressing), 16-byte items.
+template <int DT, int ROWS, int TK, int THREADS> struct AsyncGather {
+    static constexpr int CH = ElemOf<DT>::CH, ES = 16 / CH, CPR = TK / CH, TOTAL = ROWS * CPR, NL = TOTAL / THREADS;
+    static_assert(TOTAL % THREADS == 0 && (THREADS / 16) % CPR == 0, "tile does not fit the asynchronous loader");
+    struct State {
+        int32_t origin[NL];
+        uint32_t rmask[NL];
+        int32_t jlo[NL], jhi[NL];
+        int32_t r, j, dr, dj, runp, row_stride;
+    };
+    static __device__ __forceinline__ void init(State &st, const ContractArgs &g, int row0, int k0, int tid)
+    {
+        const int first = tid / CPR, pos = tid % CPR;
+        const int kk = k0 + (pos ^ chunk_swizzle<CPR>(first)) * CH;
+        st.runp = g.runp;
+        st.r = kk / g.runp;
+        st.j = kk - st.r * g.runp;
+        st.dr = TK / g.runp;
+        st.dj = TK - st.dr * g.runp;
+        st.row_stride = g.W * g.C;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int m = row0 + first + i * (THREADS / CPR);
+            const bool live = m < g.M;
+            const uint32_t um = live ? (uint32_t)m : 0u;
+            const uint32_t img = fast_div(um, g.div_hw);
+            const uint32_t rem = um - img * (uint32_t)(g.Ho * g.Wo);
+            const uint32_t p = fast_div(rem, g.div_wo), q = rem - p * (uint32_t)g.Wo;
+            const int ih0 = (int)p * g.stride_h - g.pad_h, iw0 = (int)q * g.stride_w - g.pad_w;
+            st.origin[i] = (((int)img * g.H + ih0) * g.W + iw0) * g.C;
+            const int lo = max(0, -ih0), hi = min(g.R, g.H - ih0);
+            const uint32_t below_hi = hi >= 32 ? 0xffffffffu : ((1u << max(hi, 0)) - 1u);
+            const uint32_t below_lo = (1u << min(lo, 31)) - 1u;
+            st.rmask[i] = (live && hi > lo) ? (below_hi & ~below_lo) : 0u;
+            st.jlo[i] = max(0, -iw0) * g.C;
+            st.jhi[i] = min(g.S, g.W - iw0) * g.C;
+        }
+    }
+    // Request the current slice, then step (r, j) to the next one.
+    static __device__ __forceinline__ void issue(State &st, __amdgpu_buffer_rsrc_t rsrc, uint32_t lds_tile, int R, int wave)
+    {
+        const int kterm = st.r * st.row_stride + st.j;
+        const bool r_ok = st.r < R;
+        const int rbit = st.r & 31;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const bool ok = r_ok && ((st.rmask[i] >> rbit) & 1u) && st.j >= st.jlo[i] && st.j < st.jhi[i];
+            load16_to_lds(rsrc, ok ? (uint32_t)(st.origin[i] + kterm) * (uint32_t)ES : kOutOfRange,
+                          lds_tile + (uint32_t)((i * THREADS + wave * 64) * 16));
+        }
+        st.j += st.dj;
+        st.r += st.dr;
+        if (st.j >= st.runp) {
+            st.j -= st.runp;
+            st.r += 1;
+        }
+    }
+};
+
+// Conv (16-byte gathers) and dense family with the asynchronous pipeline; g.stages = 3 or 4 buffers.
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF>
+__global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_kernel(const ContractArgs g)
+{
+    static_assert(FAM == FAM_CONV || FAM == FAM_GEMM_TN, "family without an asynchronous loader");
+    using E = typename ElemOf<DT>::type;
+    constexpr int CH = ElemOf<DT>::CH, ES = (int)sizeof(E);
+    constexpr int THREADS = (TM / WM) * (TN / WN) * 64;
+    constexpr int RB = TK * ES, CPR = TK / CH; // unpadded row
+    constexpr int A_BYTES = TM * RB, STAGE_BYTES = (TM + TN) * RB;
+    constexpr int NWR = TM / WM;
+    constexpr int NI = WM / MF, NJ = WN / MF;
+    constexpr int LG = 64 / MF, KS = CH * LG, NKS = TK / KS;
+    constexpr int ACC = MF * MF / 64;
+    constexpr bool CONV = FAM == FAM_CONV;
+    using M = Mma<DT, MF>;
+    using ARows = AsyncRows<DT, TM, TK, THREADS>;
+    using AGat = AsyncGather<DT, TM, TK, THREADS>;
+    using BRows = AsyncRows<DT, TN, TK, THREADS>;
+    constexpr int LPS = ARows::NL + BRows::NL; // loads per slice and thread
+    static_assert(2 * LPS < 64, "too many loads in flight for the counter");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t lds0 = lds_address(smem);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
+    const int k_end = tc.k0 + tc.k_ext;
+    const int kt_count = (tc.k_ext + TK - 1) / TK;
+    const int bidx = tc.hi;
+    const int nst = g.stages;
+
+    // per-batch views of the operands; the caller has checked that each fits the 2 GiB offset range
+    const E *a_base = static_cast<const E *>(g.a), *b_base = static_cast<const E *>(g.b);
+    if constexpr (!CONV) {
+        a_base += (int64_t)bidx * g.M * g.K;
+        b_base += (int64_t)bidx * g.N * g.K;
+    }
+    const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a_base, CONV ? g.a_bytes : (uint32_t)(g.M * g.K * ES));
+    const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(b_base, (uint32_t)(g.N * g.K * ES));
+
+    typename ARows::State a_rows;
+    typename AGat::State a_gat;
+    typename BRows::State b_rows;
+    if constexpr (CONV)
+        AGat::init(a_gat, g, tc.m0, tc.k0, tid);
+    else
+        ARows::init(a_rows, g.K, tc.m0, g.M, tid);
+    BRows::init(b_rows, g.K, tc.n0, g.N, tid);
+
+    // slices are requested in order
+    auto request = [&](int kt, int stage) {
+        const int k0 = tc.k0 + kt * TK;
+        const uint32_t sa = lds0 + (uint32_t)(stage * STAGE_BYTES);
+        if constexpr (CONV)
+            AGat::issue(a_gat, a_rsrc, sa, g.R, wave);
+        else
+            ARows::issue(a_rows, a_rsrc, sa, k0, k_end, wave);
+        BRows::issue(b_rows, b_rsrc, sa + A_BYTES, k0, k_end, wave);
+    };
+
+    typename M::Acc acc[NI][NJ];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int v = 0; v < ACC; ++v) acc[i][j][v] = 0.0f;
+
+    const int wr = wave % NWR, wc = wave / NWR;
+    const int lane_r = lane % MF, lane_g = lane / MF;
+    const int swz = chunk_swizzle<CPR>(lane_r);
+    const int a_row = (wr * WM + lane_r) * RB, b_row = (wc * WN + lane_r) * RB;
+
+    auto k_step = [&](const unsigned char *sa, const unsigned char *sb, int ks) {
+        const int at = ((ks * LG + lane_g) ^ swz) * 16;
+        u32x4 rf[NI], cf[NJ];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) rf[i] = *reinterpret_cast<const u32x4 *>(sa + a_row + i * MF * RB + at);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) cf[j] = *reinterpret_cast<const u32x4 *>(sb + b_row + j * MF * RB + at);
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) M::run(acc[i][j], rf[i], cf[j]);
+    };
+
+    // prologue: fill all but one buffer
+    int requested = 0;
+    for (; requested < nst - 1 && requested < kt_count; ++requested) request(requested, requested);
+    int cur = 0, fill = requested == nst - 1 ? nst - 1 : 0; // buffer to compute on / buffer the next request goes to
+    const bool unrolled = g.unroll >= 2;
+    for (int it = 0; it < kt_count; ++it) {
+        // slice `it` has arrived once at most (requested - it - 1) younger slices are outstanding
+        const int younger = requested - it - 1;
+        if (younger >= 2)
+            wait_loads_outstanding<2 * LPS>();
+        else if (younger == 1)
+            wait_loads_outstanding<LPS>();
+        else
+            wait_loads_outstanding<0>();
+        __syncthreads(); // slice `it` is visible to all waves, and all waves are done with slice it - 1
+        if (requested < kt_count) {
+            request(requested, fill);
+            ++requested;
+            fill = fill + 1 == nst ? 0 : fill + 1;
+        }
+        const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
+        if (unrolled || NKS == 1) {
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+        } else {
+#pragma unroll 1
+            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+        }
+        cur = cur + 1 == nst ? 0 : cur + 1;
+    }
+    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane);
 }
 
 template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int AM>
@@ -678,6 +938,25 @@ int launch_contract(const ContractArgs &args, int grid, int lds_bytes, void *str
     hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds_bytes, static_cast<hipStream_t>(stream), args);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : note_hip_error((int)e, "contract_kernel launch");
+}
+
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF>
+int launch_contract_async(const ContractArgs &args, int grid, int lds_bytes, void *stream)
+{
+    auto kern = contract_async_kernel<DT, FAM, TM, TN, TK, WM, WN, MF>;
+    constexpr int EPI_BYTES = (TM / WM) * (TN / WN) * MF * (WN + (MF == 32 ? 8 : 4)) * 4;
+    if (lds_bytes < EPI_BYTES) lds_bytes = EPI_BYTES;
+    static int raised = 0;
+    if (lds_bytes > 48 * 1024 && lds_bytes > raised) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return note_hip_error((int)e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+        raised = lds_bytes;
+    }
+    constexpr int THREADS = (TM / WM) * (TN / WN) * 64;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds_bytes, static_cast<hipStream_t>(stream), args);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : note_hip_error((int)e, "contract_async_kernel launch");
 }
 
 } // namespace tt

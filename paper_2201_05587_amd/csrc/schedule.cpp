@@ -73,7 +73,7 @@ bool record_well_formed(const tt_schedule &r)
     if (r.sketch < TT_SK_MFMA || r.sketch > TT_SK_DIRECT) return false;
     if (r.split_k < 1 || r.order < 0 || r.order >= 6) return false;
     if (r.vec != 1 && r.vec != 2 && r.vec != 4 && r.vec != 8) return false;
-    if (r.unroll < 1 || (r.stages != 1 && r.stages != 2)) return false;
+    if (r.unroll < 1 || r.stages < 1 || r.stages > (r.sketch == TT_SK_MFMA ? 4 : 2)) return false;
     switch (r.sketch) {
     case TT_SK_MFMA: {
         if (r.mfma != 16 && r.mfma != 32) return false;
@@ -149,12 +149,12 @@ int family_of(int cls, int trans_b)
     return FAM_GEMM_TN;
 }
 
-int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode)
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode, int pipe)
 {
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         if (v.dtype == dtype && v.family == family && v.tile_m == tm && v.tile_n == tn && v.tile_k == tk &&
-            v.wave_m == wm && v.wave_n == wn && v.mfma == mf && v.amode == amode)
+            v.wave_m == wm && v.wave_n == wn && v.mfma == mf && v.amode == amode && v.pipe == pipe)
             return i;
     }
     return -1;
@@ -330,18 +330,6 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     p.eff_split_k = cdiv(p.k_tiles, p.k_iters);
     int trans_b = 1;
     if (!is_conv_class(cls)) trans_b = static_cast<const tt_gemm_shape *>(shape)->trans_b;
-    // Staged tiles.  An operand that is contiguous along K (NHWC activations and KRSC filters
-    // included) is kept row-major with 16 bytes of row padding; the [K][N] matrix of a non-transposed
-    // batch matmul is kept K-major with a row padding that depends on the data type and the block.
-    auto rowk_bytes = [&](int rows) { return (int64_t)rows * (r.tile_k + 16 / elem) * elem; };
-    auto kmajor_bytes = [&](int cols) {
-        const int pad = dt == TT_BF16 ? (32 + 64 - cols % 64) % 64 : (r.mfma == 32 ? 8 : 4);
-        return (int64_t)r.tile_k * (cols + pad) * elem;
-    };
-    const int64_t a_bytes = rowk_bytes(r.tile_m);
-    const int64_t b_bytes = trans_b ? rowk_bytes(r.tile_n) : kmajor_bytes(r.tile_n);
-    const int64_t lds = (int64_t)r.stages * (a_bytes + b_bytes);
-    if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
     if (is_conv_class(cls)) {
         // vectors run along the channel axis of both operands and along the output channels
         const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
@@ -352,29 +340,64 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         p.eff_vec_b = trans_b ? widest_dividing(vmax, e.K) : widest_dividing(vmax, e.N);
         p.eff_vec_c = widest_dividing(vmax, e.N);
     }
-    p.slabs = e.batch * p.eff_split_k;
-    const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.slabs;
-    if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
-    p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
-    p.grid = (int)grid;
     p.block = 64 * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
-    p.lds_bytes = (int)lds;
-    p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
-    // How the conv kernels fetch their operands: 16-byte gathers when the effective vector width
-    // fills an item, else element by element.  A unit-stride 1x1 convolution without padding reads
+    // How the kernels fetch their operands.  Conv: 16-byte gathers when the effective vector width
+    // fills an item, else element by element; a unit-stride 1x1 convolution without padding reads
     // the activations as a plain [M][C] matrix and runs on the dense family.
     int amode = 0, family = family_of(cls, trans_b);
+    bool whole_items = false; // both operands are fetched as whole 16-byte items along K
     if (is_conv_class(cls)) {
         const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
         const bool pointwise = s->r == 1 && s->s == 1 && s->pad_h == 0 && s->pad_w == 0 && s->stride_h == 1 &&
                                s->stride_w == 1;
         amode = p.eff_vec_a * elem == 16 ? 16 : elem;
+        whole_items = amode == 16;
         if (pointwise && amode == 16) {
             family = FAM_GEMM_TN;
             amode = 0;
         }
+    } else if (trans_b) {
+        whole_items = p.eff_vec_a * elem == 16;
     }
-    p.variant_id = find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode);
+    // Three or four stages ask for the asynchronous pipeline: 16-byte loads straight into a ring of
+    // unpadded LDS buffers.  It needs whole items, operands within 2 GiB, whole loads per thread and
+    // a workgroup that covers whole groups of 16 tile rows; a record that asks for it where it does
+    // not apply is reformulated to the two-stage register pipeline (Section 4.1 treats unroll
+    // depths the same way).
+    const int chunks = r.tile_k * elem / 16;
+    // (the conv entry point refuses tensors of 2 GiB and more for every matrix-core record)
+    const bool in_range = is_conv_class(cls) ||
+                          ((int64_t)e.M * e.K * elem < (1ll << 31) && (int64_t)e.N * e.K * elem < (1ll << 31));
+    const bool ring_fits = whole_items && in_range && (r.tile_m * chunks) % p.block == 0 &&
+                           (r.tile_n * chunks) % p.block == 0 && (p.block / 16) % chunks == 0;
+    if (r.stages >= 3 && !ring_fits) p.stages = 2;
+    // Staged tiles.  The register pipeline keeps an operand that is contiguous along K (NHWC
+    // activations and KRSC filters included) row-major with 16 bytes of row padding, and the [K][N]
+    // matrix of a non-transposed batch matmul K-major with a row padding that depends on the data
+    // type and the block.  The asynchronous ring holds unpadded row-major tiles.
+    auto rowk_bytes = [&](int rows) { return (int64_t)rows * (r.tile_k + 16 / elem) * elem; };
+    auto kmajor_bytes = [&](int cols) {
+        const int pad = dt == TT_BF16 ? (32 + 64 - cols % 64) % 64 : (r.mfma == 32 ? 8 : 4);
+        return (int64_t)r.tile_k * (cols + pad) * elem;
+    };
+    int64_t lds;
+    if (p.stages >= 3) {
+        lds = (int64_t)p.stages * (r.tile_m + r.tile_n) * r.tile_k * elem;
+    } else {
+        const int64_t a_bytes = rowk_bytes(r.tile_m);
+        const int64_t b_bytes = trans_b ? rowk_bytes(r.tile_n) : kmajor_bytes(r.tile_n);
+        lds = (int64_t)p.stages * (a_bytes + b_bytes);
+    }
+    if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
+    p.slabs = e.batch * p.eff_split_k;
+    const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.slabs;
+    if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+    p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
+    p.grid = (int)grid;
+    p.lds_bytes = (int)lds;
+    p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
+    p.variant_id = find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode,
+                                p.stages >= 3 ? 1 : 0);
     *plan = p;
     return TT_OK;
 }
@@ -401,12 +424,12 @@ extern "C" int64_t tt_debug_fast_div(uint32_t n, uint32_t d)
     return (int64_t)fast_div(n, make_fastdiv(d));
 }
 
-extern "C" int tt_variant_info(int variant_id, int32_t out[9])
+extern "C" int tt_variant_info(int variant_id, int32_t out[10])
 {
     if (!out || variant_id < 0 || variant_id >= kNumVariants) return TT_ERR_BAD_ARG;
     const Variant &v = kVariants[variant_id];
-    const int32_t vals[9] = {v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode};
-    std::copy(vals, vals + 9, out);
+    const int32_t vals[10] = {v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode, v.pipe};
+    std::copy(vals, vals + 10, out);
     return TT_OK;
 }
 
@@ -475,13 +498,17 @@ extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out
             if (!fam_ok) continue;
             // batch matmul records do not carry the layout: list each tile once (TN and NN tables are the same)
             if (cls == TT_BATCH_MATMUL && v.family == FAM_GEMM_NN) continue;
-            if (v.family == FAM_CONV && v.amode != 16) continue; // one record per tile, whatever the fetch mode
+            if (v.pipe != 0 || (v.family == FAM_CONV && v.amode != 16)) continue; // one pass per tile
             static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 32};
             const int n_split = level >= 1 ? 9 : 1;
             const int n_order = level >= 2 ? 6 : (level >= 1 ? 2 : 1);
             for (int si = 0; si < n_split; ++si)
                 for (int order = 0; order < n_order; ++order)
-                    for (int stages = (level >= 1 ? 1 : 2); stages <= 2; ++stages) {
+                    for (int stages = (level >= 1 ? 1 : 2); stages <= (level >= 1 ? 4 : 2); ++stages) {
+                        // three and four stages only for tiles the asynchronous pipeline can load
+                        if (stages >= 3 && find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n,
+                                                        v.mfma, v.amode, 1) < 0)
+                            continue;
                         tt_schedule r = make_record(cls, TT_SK_MFMA, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n,
                                                     v.mfma, splits[si], order, vfull, 8, stages);
                         if (record_well_formed(r)) recs.push_back(r);

@@ -161,13 +161,14 @@ struct DwArgs {
 struct Variant {
     int32_t dtype, family, tile_m, tile_n, tile_k, wave_m, wave_n, mfma;
     int32_t amode; // conv family: bytes per gathered load (16 or the element size); 0 otherwise
+    int32_t pipe;  // 0: register-staged loads, 1 or 2 LDS stages; 1: asynchronous loads into a ring of 3 or 4
     int (*launch)(const ContractArgs &args, int grid, int lds_bytes, void *stream);
 };
 
 // variant table (generated) and lookups
 extern const Variant kVariants[];
 extern const int kNumVariants;
-int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode);
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode, int pipe);
 int family_of(int cls, int trans_b);
 
 // launchers of the non-matrix-core kernels (simple_kernels.hip)

@@ -126,6 +126,46 @@ def test_conv_padding_wider_than_filter_centre(api, P):
         P.check_kernel(k, [None, mfma(api, k.cls, 32, 16, tk, 16, 16, 16), mfma(api, k.cls, 64, 16, tk, 16, 16, 16)])
 
 
+# ---- asynchronous ring pipeline (3 or 4 stages) ----------------------------------------------------------
+@pytest.mark.parametrize("dt", [wl.F32, wl.BF16])
+def test_async_ring_conv(api, P, dt):
+    cls = wl.CLS_CONV2D_BIAS_ADD_RELU
+    tk = 16 if dt == wl.F32 else 32
+    for dims in ((2, 64, 28, 128, 3, 1),      # 3x3 with padding, K = 576: many slices
+                 (3, 32, 15, 96, 3, 2),       # odd map, stride 2, ragged M and N tiles
+                 (2, 16, 12, 64, 5, 1),       # 5x5: runs of 80 elements, slices straddle filter rows
+                 (2, 64, 14, 64, 1, 1),       # unit-stride 1x1: dense family, K = 64 (fewer slices than stages)
+                 (2, 128, 14, 64, 1, 2)):     # strided 1x1: gathered
+        k = conv_kernel(cls, *dims, dtype=dt)
+        scheds = [mfma(api, cls, 64, 64, tk, 32, 32, 16, stages=3), mfma(api, cls, 64, 64, tk * 2, 32, 32, 32, stages=4),
+                  mfma(api, cls, 128, 64, tk * 2, 64, 32, 32, stages=3, split_k=2, order=4),
+                  mfma(api, cls, 32, 32, tk, 16, 16, 16, stages=4, unroll=1),
+                  mfma(api, cls, 64, 64, tk * 2, 32, 32, 32, stages=4, vec=2)]   # reformulated to two stages
+        on_ring = 0
+        for s_ in scheds:
+            plan = api.tt_schedule_apply(s_, k.cls, k.shape)
+            if plan.status == api.TT_OK and plan.stages >= 3:
+                assert api.variant_name(plan).startswith("tt::contract_async_kernel")
+                on_ring += 1
+        assert on_ring >= 2, k.name   # the 32 x 32 tile (too few items per thread) and vec = 2 fall back to two stages
+        P.check_kernel(k, scheds, seed=31)
+
+
+def test_async_ring_dense_and_batch_matmul(api, P):
+    for dt in (wl.F32, wl.BF16):
+        tk = 16 if dt == wl.F32 else 32
+        k = wl.Kernel(wl.CLS_DENSE_BIAS_GELU, wl.GemmShape(1, 200, 264, 328, 1, dt), 1, f"dense_async_{dt}")
+        P.check_kernel(k, [mfma(api, k.cls, 64, 64, tk * 2, 32, 32, 32, stages=3), mfma(api, k.cls, 128, 128, tk, 64, 64, 32, stages=4),
+                           mfma(api, k.cls, 32, 32, tk, 16, 16, 16, stages=3, split_k=3)])
+        b = wl.Kernel(wl.CLS_BATCH_MATMUL, wl.GemmShape(5, 128, 72, 96, 1, dt), 1, f"bmm_async_{dt}")
+        P.check_kernel(b, [mfma(api, b.cls, 64, 64, tk, 32, 32, 32, stages=4), mfma(api, b.cls, 32, 32, tk * 2, 16, 16, 16, stages=3, order=4)])
+        # K not a multiple of the 16-byte items: the ring does not apply and the record runs with two stages
+        odd = wl.Kernel(wl.CLS_DENSE_BIAS_RELU, wl.GemmShape(1, 70, 90, 150, 1, dt), 1, f"dense_oddk_{dt}")
+        rec = mfma(api, odd.cls, 32, 32, tk, 16, 16, 16, stages=3)
+        assert api.tt_schedule_apply(rec, odd.cls, odd.shape).stages == 2
+        P.check_kernel(odd, [rec])
+
+
 # ---- dense / batch matmul -------------------------------------------------------------------------
 def test_dense_classes(api, P):
     for cls in (wl.CLS_DENSE_ADD, wl.CLS_DENSE_BIAS_RELU, wl.CLS_DENSE_BIAS_GELU):

@@ -60,7 +60,7 @@ def random_record(rng, cls):
     mf = rng.choice([16, 32])
     return S.record(cls, S.SK_MFMA, tm, tn, rng.choice([16, 32, 64, 128]), rng.choice([16, 32, 64, 128]),
                     rng.choice([16, 32, 64, 128]), mf, rng.choice([1, 1, 2, 3, 4, 8, 16, 64]), rng.randrange(6),
-                    rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 512]), rng.choice([1, 2]))
+                    rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 512]), rng.choice([1, 2, 3, 4]))
 
 
 def test_apply_matches_oracle_bit_for_bit_on_random_records():

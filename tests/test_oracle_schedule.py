@@ -156,6 +156,35 @@ def test_vector_width_and_unroll_are_reformulated_not_rejected():
     assert (p["eff_vec_a"], p["eff_vec_c"], p["K"]) == (4, 8, 40)   # 36 = 4 * 9; 36 rounded up to 8-element items
 
 
+def test_ring_stages_apply_to_whole_item_operands_and_are_reformulated_elsewhere():
+    bf = S.DT_BF16
+    conv = S.conv_shape(32, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, bf)
+    rec = S.record(E, S.SK_MFMA, 64, 64, 64, 32, 32, 32, 1, 0, 8, 8, 4)
+    p = S.apply(rec, E, conv)
+    # four unpadded buffers of (64 + 64) rows x 64 bf16
+    assert (p["status"], p["stages"], p["lds_bytes"]) == (S.OK, 4, 4 * 128 * 64 * 2)
+    # a narrower vector knob gathers element by element: no ring, two padded stages
+    p = S.apply(dict(rec, vec=4), E, conv)
+    assert (p["stages"], p["lds_bytes"]) == (2, 2 * 128 * (64 + 8) * 2)
+    # 3 input channels never fill an item
+    stem = S.conv_shape(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, bf)
+    assert S.apply(rec, E, stem)["stages"] == 2
+    # the [K][N] operand of a non-transposed batch matmul stays on the register pipeline
+    bm = S.CLS_BATCH_MATMUL
+    r7 = dict(rec, cls=bm, stages=3)
+    assert S.apply(r7, bm, S.gemm_shape(4, 128, 128, 64, 0, bf))["stages"] == 2
+    assert S.apply(r7, bm, S.gemm_shape(4, 128, 128, 64, 1, bf))["stages"] == 3
+    # 64 threads cannot cover whole 16-row groups of 8-chunk rows: (64 / 16) % 8 != 0
+    one_wave = S.record(E, S.SK_MFMA, 32, 32, 64, 32, 32, 32, 1, 0, 8, 8, 3)
+    assert S.apply(one_wave, E, conv)["stages"] == 2
+    # five stages is not a record
+    assert S.apply(dict(rec, stages=5), E, conv)["status"] == S.ERR_BAD_ARG
+    # the ring can exceed the LDS budget where two stages fit
+    big = S.record(E, S.SK_MFMA, 256, 128, 64, 64, 64, 32, 1, 0, 8, 8, 4)
+    wide = S.conv_shape(32, 64, 56, 56, 256, 3, 3, 1, 1, 1, 1, bf)
+    assert S.apply(big, E, wide)["reason"] == S.R_LDS and S.apply(dict(big, stages=3), E, wide)["status"] == S.OK
+
+
 def test_malformed_records_and_shapes_are_argument_errors():
     assert S.apply(S.record(E, wave_m=48), E, cfg1_shape())["status"] == S.ERR_BAD_ARG
     assert S.apply(S.record(E, mfma=8), E, cfg1_shape())["status"] == S.ERR_BAD_ARG
