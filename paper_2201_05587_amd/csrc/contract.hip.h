@@ -20,6 +20,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "tt_internal.h"
 
 namespace tt {
@@ -290,15 +292,15 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
         const int rbit = st.r & 31;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const bool row_ok = r_ok && ((st.rmask[i] >> rbit) & 1u);
+            const bool row_ok = r_ok & (((st.rmask[i] >> rbit) & 1u) != 0);
             const uint32_t at = (uint32_t)(st.origin[i] + kterm) * (uint32_t)ES;
             if constexpr (VEC) {
-                const bool ok = row_ok && st.j >= st.jlo[i] && st.j < st.jhi[i];
+                const bool ok = row_ok & (st.j >= st.jlo[i]) & (st.j < st.jhi[i]);
                 st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ok ? at : kOutOfRange, 0, 0);
             } else {
 #pragma unroll
                 for (int e = 0; e < CH; ++e) {
-                    const bool ok = row_ok && st.j + e >= st.jlo[i] && st.j + e < st.jhi[i];
+                    const bool ok = row_ok & (st.j + e >= st.jlo[i]) & (st.j + e < st.jhi[i]);
                     const uint32_t off = ok ? at + (uint32_t)(e * ES) : kOutOfRange;
                     if constexpr (DT == TT_F32) {
                         st.raw[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0);
@@ -646,27 +648,34 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     fetch(0);
     stash(0, 0);
     __syncthreads();
-    int cur = 0;
     const bool two_stage = g.stages == 2;
-    const bool unrolled = g.unroll >= 2;
-    for (int it = 0; it < kt_count; ++it) {
-        const bool more = it + 1 < kt_count;
-        if (more) fetch(it + 1);
-        const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
-        if (unrolled || NKS == 1) {
+    // The unroll knob picks one of two complete K loops: a choice inside the loop would make the
+    // compiler shuttle the accumulators between the register sets of the two paths on every slice.
+    auto k_loop = [&](auto unroll_steps) {
+        int cur = 0;
+        for (int it = 0; it < kt_count; ++it) {
+            const bool more = it + 1 < kt_count;
+            if (more) fetch(it + 1);
+            const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
+            if constexpr (decltype(unroll_steps)::value) {
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
-        } else {
+                for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+            } else {
 #pragma unroll 1
-            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+                for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+            }
+            if (more) {
+                if (!two_stage) __syncthreads();
+                stash(two_stage ? cur ^ 1 : 0, it + 1);
+            }
+            __syncthreads();
+            if (two_stage) cur ^= 1;
         }
-        if (more) {
-            if (!two_stage) __syncthreads();
-            stash(two_stage ? cur ^ 1 : 0, it + 1);
-        }
-        __syncthreads();
-        if (two_stage) cur ^= 1;
-    }
+    };
+    if (NKS == 1 || g.unroll >= 2)
+        k_loop(std::true_type{});
+    else
+        k_loop(std::false_type{});
 
     write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane);
 }
@@ -786,7 +795,7 @@ template <int DT, int ROWS, int TK, int THREADS> struct AsyncGather {
         const int rbit = st.r & 31;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const bool ok = r_ok && ((st.rmask[i] >> rbit) & 1u) && st.j >= st.jlo[i] && st.j < st.jhi[i];
+            const bool ok = r_ok & (((st.rmask[i] >> rbit) & 1u) != 0) & (st.j >= st.jlo[i]) & (st.j < st.jhi[i]);
             load16_to_lds(rsrc, ok ? (uint32_t)(st.origin[i] + kterm) * (uint32_t)ES : kOutOfRange,
                           lds_tile + (uint32_t)((i * THREADS + wave * 64) * 16));
         }
@@ -890,33 +899,40 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     // prologue: fill all but one buffer
     int requested = 0;
     for (; requested < nst - 1 && requested < kt_count; ++requested) request(requested, requested);
-    int cur = 0, fill = requested == nst - 1 ? nst - 1 : 0; // buffer to compute on / buffer the next request goes to
-    const bool unrolled = g.unroll >= 2;
-    for (int it = 0; it < kt_count; ++it) {
-        // slice `it` has arrived once at most (requested - it - 1) younger slices are outstanding
-        const int younger = requested - it - 1;
-        if (younger >= 2)
-            wait_loads_outstanding<2 * LPS>();
-        else if (younger == 1)
-            wait_loads_outstanding<LPS>();
-        else
-            wait_loads_outstanding<0>();
-        __syncthreads(); // slice `it` is visible to all waves, and all waves are done with slice it - 1
-        if (requested < kt_count) {
-            request(requested, fill);
-            ++requested;
-            fill = fill + 1 == nst ? 0 : fill + 1;
-        }
-        const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
-        if (unrolled || NKS == 1) {
+    // The unroll knob picks one of two complete K loops (a choice inside the loop would make the
+    // compiler shuttle the accumulators between the register sets of the two paths on every slice).
+    auto k_loop = [&](auto unroll_steps) {
+        int cur = 0, fill = requested == nst - 1 ? nst - 1 : 0; // buffer to compute on / buffer the next request fills
+        for (int it = 0; it < kt_count; ++it) {
+            // slice `it` has arrived once at most (requested - it - 1) younger slices are outstanding
+            const int younger = requested - it - 1;
+            if (younger >= 2)
+                wait_loads_outstanding<2 * LPS>();
+            else if (younger == 1)
+                wait_loads_outstanding<LPS>();
+            else
+                wait_loads_outstanding<0>();
+            __syncthreads(); // slice `it` is visible to all waves, and all waves are done with slice it - 1
+            if (requested < kt_count) {
+                request(requested, fill);
+                ++requested;
+                fill = fill + 1 == nst ? 0 : fill + 1;
+            }
+            const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
+            if constexpr (decltype(unroll_steps)::value) {
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
-        } else {
+                for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+            } else {
 #pragma unroll 1
-            for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+                for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+            }
+            cur = cur + 1 == nst ? 0 : cur + 1;
         }
-        cur = cur + 1 == nst ? 0 : cur + 1;
-    }
+    };
+    if (NKS == 1 || g.unroll >= 2)
+        k_loop(std::true_type{});
+    else
+        k_loop(std::false_type{});
     write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane);
 }
 
