@@ -154,6 +154,22 @@ template <int DT> __device__ __forceinline__ u32x4 keep_first(u32x4 v, int keep)
     return v;
 }
 
+// Zero the elements of a 16-byte item at positions outside [lo, hi).
+template <int DT> __device__ __forceinline__ u32x4 keep_range(u32x4 v, int lo, int hi)
+{
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        if constexpr (DT == TT_F32) {
+            v[h] = ((h >= lo) & (h < hi)) ? v[h] : 0u;
+        } else {
+            const uint32_t low = ((2 * h >= lo) & (2 * h < hi)) ? 0xffffu : 0u;
+            const uint32_t high = ((2 * h + 1 >= lo) & (2 * h + 1 < hi)) ? 0xffff0000u : 0u;
+            v[h] &= low | high;
+        }
+    }
+    return v;
+}
+
 // Rows of a K-contiguous matrix [rows_total][K], K >= CH: each thread fetches 16-byte chunks along
 // K.  A chunk that would run past the end of its row is read CH elements back from the row end
 // and shifted down afterwards, so the access never leaves the matrix.
@@ -215,10 +231,13 @@ template <int DT, int ROWS, int TK, int THREADS> struct RowKLoader {
 // part of the run that falls inside the image row; everything else is zero padding.
 //
 // With VEC an item is one 16-byte load: C is a multiple of the items' element count, so an item
-// lies inside one pixel and is real or padding as a whole.  Without VEC (the 3-channel stem) an
-// item is gathered element by element, each with its own bounds, and the run is padded up to
-// whole items (runp > run).  The same loader reads the filter matrix in that case (WEIGHTS):
-// rows are output channels, origin = n * R * run, every filter row is real and j < run.
+// lies inside one pixel and is real or padding as a whole.  Without VEC (the 3-channel stem) the
+// run is padded up to whole items (runp > run) and an item may be real in part: it is still one
+// 16-byte load, at element alignment, and the store step zeroes the elements outside [jlo, jhi).
+// Only an item that would begin before the tensor or end after it (where the bounds check works on
+// whole 4-byte words) is gathered element by element.  The same loader reads the filter matrix
+// in that case (WEIGHTS): rows are output channels, origin = n * R * run, every filter row is real
+// and j < run.
 //
 // All rows a thread loads share one chunk of the slice (THREADS is a multiple of the chunks per
 // row), so (r, j) is one pair per thread, advanced by add-and-carry from slice to slice.
@@ -241,14 +260,16 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
         int32_t origin[NL];  // element offset of (tap (0,0), channel 0) / of the filter's first element
         uint32_t rmask[NL];  // bit r set: filter row r of this tile row is real (0 for rows past the matrix)
         int32_t jlo[NL], jhi[NL];
-        int32_t r, j, dr, dj, runp, row_stride;
+        int32_t r, j, dr, dj, runp, row_stride, numel;
         u32x4 raw[NL];
+        int32_t span[NL]; // without VEC: first real element of the item in flight | (one past the last) << 8
     };
 
     static __device__ __forceinline__ void init(State &st, const ContractArgs &g, int row0, int k0, int tid)
     {
         const int chunk = tid % CPR, first = tid / CPR;
         const int kk = k0 + chunk * CH;
+        st.numel = (int32_t)((WEIGHTS ? g.b_bytes : g.a_bytes) / (uint32_t)ES);
         st.runp = g.runp;
         st.r = kk / g.runp;
         st.j = kk - st.r * g.runp;
@@ -298,18 +319,27 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
                 const bool ok = row_ok & (st.j >= st.jlo[i]) & (st.j < st.jhi[i]);
                 st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ok ? at : kOutOfRange, 0, 0);
             } else {
+                // real elements of this item: [lo, hi) relative to its first element
+                const int lo = min(max(st.jlo[i] - st.j, 0), CH), hi = min(max(st.jhi[i] - st.j, 0), CH);
+                const bool any = row_ok & (hi > lo);
+                const int start = st.origin[i] + kterm;
+                st.span[i] = any ? (lo | (hi << 8)) : 0;
+                if (!any || (start >= 0 && start + CH <= st.numel)) {
+                    st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, any ? at : kOutOfRange, 0, 0);
+                } else {
+                    // the first or the last item of the whole tensor: element by element
 #pragma unroll
-                for (int e = 0; e < CH; ++e) {
-                    const bool ok = row_ok & (st.j + e >= st.jlo[i]) & (st.j + e < st.jhi[i]);
-                    const uint32_t off = ok ? at + (uint32_t)(e * ES) : kOutOfRange;
-                    if constexpr (DT == TT_F32) {
-                        st.raw[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0);
-                    } else {
-                        const uint32_t v = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, off, 0, 0);
-                        if (e % 2 == 0)
-                            st.raw[i][e / 2] = v;
-                        else
-                            st.raw[i][e / 2] |= v << 16;
+                    for (int e = 0; e < CH; ++e) {
+                        const uint32_t off = ((e >= lo) & (e < hi)) ? at + (uint32_t)(e * ES) : kOutOfRange;
+                        if constexpr (DT == TT_F32) {
+                            st.raw[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0);
+                        } else {
+                            const uint32_t v = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, off, 0, 0);
+                            if (e % 2 == 0)
+                                st.raw[i][e / 2] = v;
+                            else
+                                st.raw[i][e / 2] |= v << 16;
+                        }
                     }
                 }
             }
@@ -329,7 +359,9 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
         for (int i = 0; i < NL; ++i) {
             const int row = first + i * STEP;
             if (TOTAL % THREADS != 0 && row >= ROWS) continue;
-            *reinterpret_cast<u32x4 *>(lds + row * ROWB + chunk * 16) = st.raw[i];
+            u32x4 v = st.raw[i];
+            if constexpr (!VEC) v = keep_range<DT>(v, st.span[i] & 0xff, st.span[i] >> 8);
+            *reinterpret_cast<u32x4 *>(lds + row * ROWB + chunk * 16) = v;
         }
     }
 };
@@ -423,99 +455,116 @@ template <int DT, int MF, int LEN> __device__ __forceinline__ u32x4 kmajor_fragm
 // bias, residual, activation and down-conversion then work on 16-byte vectors (or on the widest
 // sub-vectors the output's row length allows), and stores are fully coalesced.  With split-K
 // the raw partial sums go to the workspace in the same pattern.
+// Which outputs a lane owns after that transposition.
+template <int TM, int WM, int WN, int MF> struct TileOut {
+    static constexpr int NWR = TM / WM, NI = WM / MF, NJ = WN / MF, ACC = MF * MF / 64;
+    static constexpr int ESTRIDE = WN + (MF == 32 ? 8 : 4);      // floats per staged row (bank-conflict padding)
+    static constexpr int CG = WN / 8;                            // 8-column groups per row
+    static constexpr int ROWS_PER_PASS = 64 / CG;                // rows the 64 lanes cover at once
+    static constexpr int PASSES = (MF + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
+    // row of the workgroup tile / first of the 8 columns this lane handles in band i, pass ps
+    static __device__ __forceinline__ int row(int wave, int lane, int i, int ps)
+    {
+        return (wave % NWR) * WM + i * MF + ps * ROWS_PER_PASS + lane / CG;
+    }
+    static __device__ __forceinline__ int col(int wave, int lane) { return (wave / NWR) * WN + (lane % CG) * 8; }
+    static __device__ __forceinline__ bool pass_live(int lane, int ps)
+    {
+        return ROWS_PER_PASS * PASSES == MF || ps * ROWS_PER_PASS + lane / CG < MF;
+    }
+};
+
 template <int DT, int TM, int WM, int WN, int MF, typename Acc>
 __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
                                            unsigned char *smem, int wave, int lane)
 {
-    constexpr int NWR = TM / WM, NI = WM / MF, NJ = WN / MF, ACC = MF * MF / 64;
-    const int wr = wave % NWR, wc = wave / NWR;
+    using T = TileOut<TM, WM, WN, MF>;
+    constexpr int NI = T::NI, NJ = T::NJ, ACC = T::ACC, ESTRIDE = T::ESTRIDE, CG = T::CG, PASSES = T::PASSES;
     const int lane_r = lane % MF, lane_g = lane / MF;
     const int bidx = tc.hi;
-    {
-        constexpr int ESTRIDE = WN + (MF == 32 ? 8 : 4);      // floats per staged row (bank-conflict padding)
-        constexpr int CG = WN / 8;                            // 8-column groups per row
-        constexpr int ROWS_PER_PASS = 64 / CG;                // rows the 64 lanes cover at once
-        constexpr int PASSES = (MF + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
-        float *stage = reinterpret_cast<float *>(smem) + wave * (MF * ESTRIDE);
-        const bool partial = g.map.eff_split_k > 1;
-        const int64_t mn = (int64_t)g.M * g.N;
-        float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
-        const int vc = g.eff_vec_c; // consecutive outputs of a row that are all inside or all outside the matrix
-        const int cg = lane % CG, row_in_pass = lane / CG;
-        const int c0 = wc * WN + cg * 8; // first of this lane's 8 columns inside the workgroup tile
+    float *stage = reinterpret_cast<float *>(smem) + wave * (MF * ESTRIDE);
+    const bool partial = g.map.eff_split_k > 1;
+    const int64_t mn = (int64_t)g.M * g.N;
+    float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
+    const int vc = g.eff_vec_c; // consecutive outputs of a row that are all inside or all outside the matrix
+    const int cg = lane % CG;
+    const int first = tc.n0 + T::col(wave, lane);
 
+    // Every wave is done reading the operand tiles.  From here on a wave only touches its own staging
+    // region, and the LDS executes one wave's accesses in order: no further barrier is needed, only
+    // the compiler must keep the staging writes and reads in program order.
+    __syncthreads();
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            __syncthreads(); // the band before this one has been read (and the K loop is over)
+    for (int i = 0; i < NI; ++i) {
+        asm volatile("" ::: "memory"); // the reads of the band before stay ahead of these writes
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int v = 0; v < ACC; ++v) {
-                    const int row_l = MF == 32 ? (v / 4) * 8 + lane_g * 4 + (v % 4) : lane_g * 4 + v;
-                    stage[row_l * ESTRIDE + j * MF + lane_r] = acc[i][j][v];
-                }
-            __syncthreads();
+            for (int v = 0; v < ACC; ++v) {
+                const int row_l = MF == 32 ? (v / 4) * 8 + lane_g * 4 + (v % 4) : lane_g * 4 + v;
+                stage[row_l * ESTRIDE + j * MF + lane_r] = acc[i][j][v];
+            }
+        asm volatile("" ::: "memory"); // and the reads below stay behind them
 #pragma unroll
-            for (int ps = 0; ps < PASSES; ++ps) {
-                const int row_l = ps * ROWS_PER_PASS + row_in_pass;
-                if (ROWS_PER_PASS * PASSES > MF && row_l >= MF) continue;
-                const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8);
-                const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
-                float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                const int m = tc.m0 + wr * WM + i * MF + row_l;
-                if (m >= g.M) continue;
-                const int first = tc.n0 + c0;
-                // groups of vc consecutive columns
-                for (int e0 = 0; e0 < 8; e0 += vc) {
-                    const int n = first + e0;
-                    if (n >= g.N) break;
-                    const int64_t idx = (int64_t)bidx * mn + (int64_t)m * g.N + n;
-                    if (partial) {
-                        if (vc == 8) {
-                            *reinterpret_cast<f32x4 *>(ws + idx) = lo;
-                            *reinterpret_cast<f32x4 *>(ws + idx + 4) = hi;
-                        } else if (vc == 4) {
-                            *reinterpret_cast<f32x4 *>(ws + idx) = e0 == 0 ? lo : hi;
-                        } else {
-                            for (int e = 0; e < vc; ++e) ws[idx + e] = val[e0 + e];
-                        }
-                        continue;
-                    }
-                    if (vc == 8 && DT == TT_BF16) {
-                        u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
-                        if (g.has_res) resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
-                        if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
-                        u32x4 outv;
-#pragma unroll
-                        for (int h = 0; h < 4; ++h) {
-                            float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
-                            float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) +
-                                      __uint_as_float(resv[h] & 0xffff0000u);
-                            outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
-                                      ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
-                        }
-                        *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
-                    } else if (vc >= 4 && DT == TT_F32) {
-#pragma unroll
-                        for (int q4 = 0; q4 < 2; ++q4) {
-                            if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
-                            f32x4 r = q4 == 0 ? lo : hi;
-                            const int64_t at = idx + (q4 * 4 - e0);
-                            f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
-                            if (g.has_bias)
-                                add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
-                            if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
-                            *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
-                        }
+        for (int ps = 0; ps < PASSES; ++ps) {
+            if (!T::pass_live(lane, ps)) continue;
+            const int row_l = ps * T::ROWS_PER_PASS + lane / CG;
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
+            float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            const int m = tc.m0 + T::row(wave, lane, i, ps);
+            if (m >= g.M) continue;
+            // groups of vc consecutive columns
+            for (int e0 = 0; e0 < 8; e0 += vc) {
+                const int n = first + e0;
+                if (n >= g.N) break;
+                const int64_t idx = (int64_t)bidx * mn + (int64_t)m * g.N + n;
+                if (partial) {
+                    if (vc == 8) {
+                        *reinterpret_cast<f32x4 *>(ws + idx) = lo;
+                        *reinterpret_cast<f32x4 *>(ws + idx + 4) = hi;
+                    } else if (vc == 4) {
+                        *reinterpret_cast<f32x4 *>(ws + idx) = e0 == 0 ? lo : hi;
                     } else {
-                        for (int e = 0; e < vc; ++e) {
-                            float a = val[e0 + e];
-                            if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
-                            if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
-                            store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
-                        }
+                        for (int e = 0; e < vc; ++e) ws[idx + e] = val[e0 + e];
+                    }
+                    continue;
+                }
+                if (vc == 8 && DT == TT_BF16) {
+                    u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
+                    if (g.has_res)
+                        resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
+                    if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
+                    u32x4 outv;
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
+                        float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) +
+                                  __uint_as_float(resv[h] & 0xffff0000u);
+                        outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
+                                  ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
+                    }
+                    *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
+                } else if (vc >= 4 && DT == TT_F32) {
+#pragma unroll
+                    for (int q4 = 0; q4 < 2; ++q4) {
+                        if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
+                        f32x4 r = q4 == 0 ? lo : hi;
+                        const int64_t at = idx + (q4 * 4 - e0);
+                        f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (g.has_bias)
+                            add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
+                        if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
+                    }
+                } else {
+                    for (int e = 0; e < vc; ++e) {
+                        float a = val[e0 + e];
+                        if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
+                        if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
+                        store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
                     }
                 }
             }
