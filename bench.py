@@ -131,7 +131,7 @@ def main():
               "(kernel/schedule pairs are independent and would shard by target kernel, see DESIGN.md)")
         sys.exit(2)
     import torch
-    from paper_2201_05587_amd import api, harness, tune
+    from paper_2201_05587_amd import api, harness, traffic, tune
     from paper_2201_05587_amd import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs a GPU; there is no CPU fallback"
@@ -219,7 +219,9 @@ def main():
     else:
         roof = dict(bound="hbm", achieved=dom["bytes"] / dom["us"] / 1e3, peak=PEAK["hbm"], unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    # HBM bytes per launch measured with rocprofv3 counters (paper_2201_05587_amd/traffic.py), reported
+    # only while the kernel sources are the ones the counters were taken on
+    roof["traffic"] = traffic.lookup(args.workload, dom_name)
     roof.update(kernel=dom_name, avg_launch_us=dom["us"] / dom["launches"], launches=dom["launches"],
                 layers=sorted(dom["layers"]), arithmetic_intensity=ai)
     groups = {n: dict(g, layers=sorted(g["layers"]), avg_us=g["us"] / g["launches"]) for n, g in ledger.items()}
