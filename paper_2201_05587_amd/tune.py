@@ -30,7 +30,10 @@ def native_sweep(dk: api.DeviceKernel, level: int = 1, finalists: int = 4, space
     """Exhaustive sweep of the class's schedule space on the kernel's own shape.
 
     Returns (best_record, best_us, default_us, n_valid, n_records).  The space is walked with the
-    cheap protocol, the `finalists` fastest records and the default are re-timed with the full one.
+    cheap protocol; the `finalists` fastest records are then tried under every workgroup raster
+    order (the enumerated space of level 1 carries only the two plain ones; the XCD-contiguous
+    orders decide how often the L2 caches re-fetch shared operand tiles), and the fastest of those
+    and the default are re-timed with the full protocol.
     """
     dtype = dk.cshape.dtype
     if space is None:
@@ -43,6 +46,19 @@ def native_sweep(dk: api.DeviceKernel, level: int = 1, finalists: int = 4, space
     if not top:
         rc, med, _ = api.tt_time_pair(dk, None, api.make_opts(**FULL))
         return None, med, med, 0, len(space)
+    if top[0].sketch == api.TT_SK_MFMA:
+        seen, variants = set(), []
+        for rec in top:
+            for order in range(6):
+                r = rec.copy()
+                r.order = order
+                key = tuple(sorted(r.knobs().items()))
+                if key not in seen:
+                    seen.add(key)
+                    variants.append(r)
+        rows, table, _, _ = api.tt_transfer_sweep([dk], variants, api.make_opts(**EXPLORE))
+        ranked = sorted((t, i) for i, t in enumerate(table[0]) if t >= 0)
+        top = [variants[i] for _, i in ranked[:finalists]]
     rows, table, _, _ = api.tt_transfer_sweep([dk], top, api.make_opts(**FULL))
     r = rows[0]
     best = top[r["chosen"]].copy() if r["chosen"] >= 0 else None
