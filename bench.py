@@ -176,7 +176,7 @@ def main():
 
     def symbol_of(k, rec):
         rec = rec if rec is not None else api.tt_schedule_default(k.cls, k.shape)
-        return api.variant_name(api.tt_schedule_apply(rec, k.cls, k.shape))
+        return api.variant_name(api.tt_schedule_apply(rec, k.cls, k.shape), k.shape)
 
     def timed_launches(k, dk, rec):
         """Average duration of one launch of (kernel, record): use_count x reps launches between two events."""

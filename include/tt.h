@@ -135,8 +135,10 @@ typedef struct tt_gemm_shape {
  *                the ring does not apply: partial 16-byte items, [K][N] operands, odd tile/thread ratios).
  *   TT_SK_GEMV   tile_m (= wave_m) rows and tile_n outputs per workgroup, wave_n outputs per wave,
  *                tile_k = K elements a wave consumes per step (64 lanes x 1/2/4/8), mfma = 0.
- *   TT_SK_DWCONV tile_m x tile_n output rows x cols and tile_k planes per workgroup, wave_m x wave_n
- *                outputs per thread, stages = 2 stages the input patch through LDS, mfma = 0.
+ *   TT_SK_DWCONV tile_m x tile_n output rows x cols and tile_k lanes along the plane axis per workgroup,
+ *                wave_m x wave_n outputs per thread; vec = channel-contiguous planes per lane (reformulated
+ *                to what divides the channel count; the workgroup then covers tile_k * vec planes);
+ *                stages = 2 stages the input patch through LDS (one plane per lane), mfma = 0.
  *   TT_SK_DIRECT all tile and wave fields 1, mfma = 0.
  */
 typedef struct tt_schedule {

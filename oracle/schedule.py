@@ -338,6 +338,15 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
         return plan
 
     tm, tn, tk = rec["tile_m"], rec["tile_n"], rec["tile_k"]
+    ev_planes = 1
+    if sk == SK_DWCONV:
+        # Vectorize on the plane axis: a lane owns ev channel-contiguous planes, so the workgroup's
+        # tile_k lanes along that axis cover tile_k * ev planes
+        # (the register kernel only: one stage, equal strides of 1 or 2, input below 2 GiB)
+        vectorised = (rec["stages"] == 1 and shape["stride_h"] == shape["stride_w"] and shape["stride_h"] in (1, 2)
+                      and shape["n"] * shape["h"] * shape["w"] * shape["c"] * elem < 2 ** 31)
+        ev_planes = pow2_dividing(vmax, shape["c"]) if vectorised else 1
+        tk *= ev_planes
     # Inner factors are kept; a factor larger than the loop it splits is invalid (Section 4.2).
     for factor, extent, reason in ((tm, M, R_FACTOR_GT_M), (tn, N, R_FACTOR_GT_N), (tk, K, R_FACTOR_GT_K)):
         if factor > extent:
@@ -351,7 +360,7 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
                 tail_n=N - (tiles_n - 1) * tn, tail_k=K - (k_tiles - 1) * tk)
 
     if sk == SK_DWCONV:
-        threads = tk * (tm // rec["wave_m"]) * (tn // rec["wave_n"])
+        threads = rec["tile_k"] * (tm // rec["wave_m"]) * (tn // rec["wave_n"])
         lds = 0
         if rec["stages"] == 2:
             rows = (tm - 1) * shape["stride_h"] + shape["r"]
@@ -359,7 +368,7 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
             lds = tk * rows * cols * elem
         if lds > LDS_BUDGET:
             return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
-        ev = 1  # a lane owns one plane and planes are the contiguous (NHWC) axis
+        ev = ev_planes
         grid = tiles_m * tiles_n * k_tiles
         if grid >= 2 ** 31:
             return _fail(plan, ERR_INVALID_SCHEDULE, R_GRID)

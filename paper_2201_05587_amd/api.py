@@ -405,13 +405,21 @@ class KernelList:
         _check(lib.tt_run_kernels(self.descs, self.ptrs, self.n, repeat, _stream()), "tt_run_kernels")
 
 
-def variant_name(plan: tt_plan) -> str:
-    """Name of the kernel a plan launches, spelled like the demangled symbol rocprofv3 reports."""
+def variant_name(plan: tt_plan, shape=None) -> str:
+    """Name of the kernel a plan launches, spelled like the demangled symbol rocprofv3 reports.
+
+    `shape` (a conv shape) is needed only to tell the two depthwise kernels apart.
+    """
     if plan.sketch == TT_SK_MFMA:
         info = (c_int32 * 10)()
         _check(lib.tt_variant_info(plan.variant_id, byref(info)), "tt_variant_info")
         if info[9]:
             return "tt::contract_async_kernel<" + ", ".join(str(v) for v in info[:8]) + ">"
         return "tt::contract_kernel<" + ", ".join(str(v) for v in info[:9]) + ">"
-    return {TT_SK_GEMV: "tt::gemv_kernel", TT_SK_DWCONV: f"tt::dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}>",
-            TT_SK_DIRECT: "tt::direct_kernel"}[plan.sketch]
+    if plan.sketch == TT_SK_DWCONV:
+        s = shape
+        if (s is not None and plan.stages == 1 and s.stride_h == s.stride_w and s.stride_h in (1, 2)
+                and s.n * s.h * s.w * s.c * 4 < 2 ** 31):
+            return f"tt::dwconv3x3_rows_kernel<{plan.wave_m}, {plan.wave_n}, {plan.eff_vec_a}, {s.stride_h}>"
+        return f"tt::dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}>"
+    return {TT_SK_GEMV: "tt::gemv_kernel", TT_SK_DIRECT: "tt::direct_kernel"}[plan.sketch]

@@ -199,6 +199,9 @@ extern "C" int tt_dwconv(const void *x, const void *w, const void *bias, void *y
     g.wave_n = plan.wave_n;
     g.stages = plan.stages;
     g.unroll = plan.eff_unroll;
+    g.eff_vec = plan.eff_vec_a;
+    const int64_t x_bytes = (int64_t)shape->n * shape->h * shape->w * shape->c * 4;
+    g.x_bytes = x_bytes < (1ll << 31) ? (uint32_t)x_bytes : 0u;
     if (plan.sketch == TT_SK_DIRECT) return launch_dw_direct(g, plan.grid, stream);
     return launch_dwconv(g, plan, stream);
 }

@@ -261,8 +261,20 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         return TT_OK;
     }
 
+    // Depthwise: Vectorize applies to the plane axis.  A lane owns ev channel-contiguous planes, so
+    // the tile_k lanes a workgroup has along that axis cover tile_k * ev planes.
+    // (The register kernel only: one stage, equal strides of 1 or 2, input below 2 GiB.)
+    int ev_planes = 1;
+    if (r.sketch == TT_SK_DWCONV) {
+        const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
+        const bool vectorised = r.stages == 1 && s->stride_h == s->stride_w && (s->stride_h == 1 || s->stride_h == 2) &&
+                                (int64_t)s->n * s->h * s->w * s->c * elem < (1ll << 31);
+        if (vectorised) ev_planes = widest_dividing(vmax, s->c);
+    }
+    const int64_t tile_k_eff = (int64_t)r.tile_k * ev_planes;
+    if (tile_k_eff > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_FACTOR_GT_K);
     // Inner factors are kept as recorded; a factor larger than the loop it splits cannot be applied.
-    const int factor[3] = {r.tile_m, r.tile_n, r.tile_k};
+    const int factor[3] = {r.tile_m, r.tile_n, (int)tile_k_eff};
     const int extent[3] = {e.M, e.N, e.K};
     for (int i = 0; i < 3; ++i) {
         if (factor[i] > extent[i]) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_FACTOR_GT_M + i);
@@ -271,15 +283,15 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     // Outer extents come from the target shape; the last tile is guarded.
     p.tile_m = r.tile_m;
     p.tile_n = r.tile_n;
-    p.tile_k = r.tile_k;
+    p.tile_k = (int)tile_k_eff;
     p.wave_m = r.wave_m;
     p.wave_n = r.wave_n;
     p.tiles_m = cdiv(e.M, r.tile_m);
     p.tiles_n = cdiv(e.N, r.tile_n);
-    p.k_tiles = cdiv(e.K, r.tile_k);
+    p.k_tiles = cdiv(e.K, p.tile_k);
     p.tail_m = e.M - (p.tiles_m - 1) * r.tile_m;
     p.tail_n = e.N - (p.tiles_n - 1) * r.tile_n;
-    p.tail_k = e.K - (p.k_tiles - 1) * r.tile_k;
+    p.tail_k = e.K - (p.k_tiles - 1) * p.tile_k;
 
     if (r.sketch == TT_SK_DWCONV) {
         const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
@@ -287,16 +299,16 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         if (r.stages == 2) {
             const int64_t rows = (int64_t)(r.tile_m - 1) * s->stride_h + s->r;
             const int64_t cols = (int64_t)(r.tile_n - 1) * s->stride_w + s->s;
-            lds = r.tile_k * rows * cols * elem;
+            lds = p.tile_k * rows * cols * elem;
         }
         if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
         const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.k_tiles;
         if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
-        // a lane owns one plane, and planes are the contiguous axis: nothing left to vectorise
         p.eff_split_k = 1;
         p.k_iters = 1;
         p.slabs = p.k_tiles;
-        p.eff_vec_a = p.eff_vec_b = p.eff_vec_c = 1;
+        p.eff_vec_a = p.eff_vec_c = ev_planes;
+        p.eff_vec_b = 1;
         p.eff_unroll = std::min(r.unroll, r.wave_m);
         p.grid = (int)grid;
         p.block = r.tile_k * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
@@ -476,8 +488,9 @@ extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out
     std::vector<tt_schedule> recs;
     const int vfull = dtype == TT_F32 ? 4 : 8;
     if (cls == TT_DWCONV_BIAS_RELU6) {
-        static const int tms[] = {1, 2, 4, 7, 8, 14, 16}, tns[] = {7, 8, 14, 16, 28, 32, 56, 64, 112};
-        static const int tks[] = {1, 2, 4, 8, 16}, wms[] = {1, 2, 4, 7}, wns[] = {1, 2, 4, 7};
+        // planes (channels) are the contiguous axis: tiles are wide in planes and small in rows x cols
+        static const int tms[] = {1, 2, 4, 7, 8, 14}, tns[] = {1, 2, 4, 7, 8, 14, 16, 28};
+        static const int tks[] = {8, 16, 32, 64, 128, 256}, wms[] = {1, 2, 4, 7}, wns[] = {1, 2, 4, 7};
         for (int tm : tms)
             for (int tn : tns)
                 for (int tk : tks)

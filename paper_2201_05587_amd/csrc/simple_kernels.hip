@@ -202,6 +202,96 @@ template <int WM, int WN> __global__ void dwconv3x3_kernel(const DwArgs g)
     }
 }
 
+// ---- depthwise 3x3, register version: VC channel-contiguous planes per lane, unit or double stride ---
+// The same tile and thread layout as above, without LDS.  For each of its WM output rows a thread
+// fetches the three input rows it needs, each input pixel once, as VC-wide vectors through
+// bounds-checked buffer loads (an offset outside the tensor reads as zero, which is the padding),
+// then forms its WN outputs.  Lanes of a wave hold neighbouring channel groups of one pixel, so
+// every load and store instruction covers one contiguous run of memory.
+template <int WM, int WN, int VC, int STR> __global__ void dwconv3x3_rows_kernel(const DwArgs g)
+{
+    typedef __attribute__((ext_vector_type(VC))) float vec_t;
+    constexpr int COLS = (WN - 1) * STR + 3;
+    const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
+    const int lanes_k = g.map.tile_k / VC; // lanes along the plane axis
+    const int tcols = g.map.tile_n / WN;
+    const int tid = threadIdx.x;
+    const int tp = tid % lanes_k, tx = (tid / lanes_k) % tcols, ty = tid / (lanes_k * tcols);
+    const int plane = tc.k0 + tp * VC;
+    if (plane >= tc.k0 + tc.k_ext) return;
+    const int img = plane / g.C, ch = plane - img * g.C;
+    const int p0 = tc.m0 + ty * WM, q0 = tc.n0 + tx * WN;
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(g.x, g.x_bytes);
+
+    vec_t wgt[9], bias;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) wgt[i] = *reinterpret_cast<const vec_t *>(g.w + i * g.C + ch);
+#pragma unroll
+    for (int v = 0; v < VC; ++v) bias[v] = g.bias ? g.bias[ch + v] : 0.0f;
+
+    // byte offset of input column c of this thread's window, or out of range
+    const int iw0 = q0 * STR - g.pad_w;
+    uint32_t col_off[COLS];
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) {
+        const int iw = iw0 + c;
+        col_off[c] = (iw >= 0 && iw < g.W) ? (uint32_t)((iw * g.C + ch) * 4) : kOutOfRange;
+    }
+    const int plim = min(g.Ho, tc.m0 + tc.m_ext), qlim = min(g.Wo, tc.n0 + tc.n_ext);
+    float *yp = g.y + (int64_t)img * g.Ho * g.Wo * g.C + ch;
+
+    auto body = [&](int i) {
+        const int p = p0 + i;
+        if (p >= plim) return;
+        vec_t out[WN];
+#pragma unroll
+        for (int j = 0; j < WN; ++j) out[j] = bias;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int ih = p * STR + r - g.pad_h;
+            const bool row_ok = ih >= 0 && ih < g.H;
+            const uint32_t row_off = (uint32_t)((img * g.H + ih) * g.W * g.C * 4);
+            vec_t in[COLS];
+#pragma unroll
+            for (int c = 0; c < COLS; ++c) {
+                // an out-of-range column keeps its sentinel: the sum below stays out of range for every row offset
+                const uint32_t off = (row_ok && col_off[c] != kOutOfRange) ? row_off + col_off[c] : kOutOfRange;
+                if constexpr (VC == 4) {
+                    const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0, 0);
+                    in[c] = __builtin_bit_cast(vec_t, t);
+                } else if constexpr (VC == 2) {
+                    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+                    const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(xr, off, 0, 0);
+                    in[c] = __builtin_bit_cast(vec_t, t);
+                } else {
+                    in[c][0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(xr, off, 0, 0));
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+#pragma unroll
+                    for (int v = 0; v < VC; ++v) out[j][v] = fmaf(in[j * STR + s][v], wgt[r * 3 + s][v], out[j][v]);
+        }
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            if (q0 + j >= qlim) continue;
+            vec_t o;
+#pragma unroll
+            for (int v = 0; v < VC; ++v) o[v] = fminf(fmaxf(out[j][v], 0.0f), 6.0f);
+            *reinterpret_cast<vec_t *>(yp + ((int64_t)p * g.Wo + q0 + j) * g.C) = o;
+        }
+    };
+    if (g.unroll >= WM) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) body(i);
+    } else {
+#pragma unroll 1
+        for (int i = 0; i < WM; ++i) body(i);
+    }
+}
+
 __global__ void __launch_bounds__(256) dw_direct_kernel(const DwArgs g)
 {
     // idx walks the NHWC output: (image, p, q, channel)
@@ -287,13 +377,36 @@ int launch_gemv(const ContractArgs &args, const tt_plan &plan, void *stream)
     return launched();
 }
 
+namespace {
+
+template <int WM, int WN> int launch_dw_rows(const DwArgs &a, dim3 grid, dim3 block, hipStream_t s)
+{
+    const int str = a.stride_h;
+#define TT_DW_ROWS(VC_, STR_)                                                                                        \
+    if (a.eff_vec == VC_ && str == STR_) {                                                                           \
+        hipLaunchKernelGGL((dwconv3x3_rows_kernel<WM, WN, VC_, STR_>), grid, block, 0, s, a);                        \
+        return launched();                                                                                           \
+    }
+    TT_DW_ROWS(1, 1) TT_DW_ROWS(2, 1) TT_DW_ROWS(4, 1) TT_DW_ROWS(1, 2) TT_DW_ROWS(2, 2) TT_DW_ROWS(4, 2)
+#undef TT_DW_ROWS
+    return TT_ERR_UNSUPPORTED;
+}
+
+} // namespace
+
 int launch_dwconv(const DwArgs &a, const tt_plan &plan, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(plan.grid), block(plan.block);
     const int lds = plan.lds_bytes;
+    // One stage, strides 1 or 2 and a tensor within the 2 GiB offset range: the register kernel.
+    // Everything else (the LDS patch of two stages, other strides): the general kernel, one plane per lane.
+    const bool rows_kernel = a.stages == 1 && a.stride_h == a.stride_w && (a.stride_h == 1 || a.stride_h == 2) &&
+                             a.x_bytes != 0;
+    if (!rows_kernel && a.eff_vec != 1) return TT_ERR_UNSUPPORTED;
 #define TT_DW_CASE(WM_, WN_)                                                                                         \
     if (a.wave_m == WM_ && a.wave_n == WN_) {                                                                        \
+        if (rows_kernel) return launch_dw_rows<WM_, WN_>(a, grid, block, s);                                         \
         auto kern = dwconv3x3_kernel<WM_, WN_>;                                                                      \
         if (lds > 48 * 1024 &&                                                                                       \
             hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \

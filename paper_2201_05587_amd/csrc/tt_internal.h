@@ -156,6 +156,8 @@ struct DwArgs {
     TileMap map;
     int32_t planes, C, H, W, Ho, Wo, stride_h, stride_w, pad_h, pad_w;
     int32_t wave_m, wave_n, stages, unroll;
+    int32_t eff_vec;   // channel-contiguous planes per lane (1, 2 or 4)
+    uint32_t x_bytes;  // size of the input tensor when it is below 2 GiB, else 0
 };
 
 struct Variant {
