@@ -230,6 +230,25 @@ def test_depthwise_shapes_and_records(api, P):
         P.check_kernel(k, scheds)
 
 
+def test_depthwise_channel_vectors_and_general_kernel(api, P):
+    dw = lambda tm, tn, tk, wm, wn, stages=1, vec=4, unroll=8, order=0: api.make_schedule(
+        wl.CLS_DWCONV_BIAS_RELU6, api.TT_SK_DWCONV, tm, tn, tk, wm, wn, 0, 1, order, vec, unroll, stages)
+    cases = [((2, 6, 20, 20, 1, 1), 2),     # 6 channels: pairs of planes per lane
+             ((3, 5, 17, 13, 2, 2), 1),     # 5 channels: one plane per lane; odd map, stride 2
+             ((2, 24, 19, 19, 1, 1), 4),    # four planes per lane, ragged rows and columns
+             ((1, 16, 21, 21, 3, 3), 1),    # stride 3: the general kernel, nothing vectorised
+             ((2, 8, 18, 18, 2, 1), 1)]     # unequal strides: the general kernel
+    for (n, c, h, w, sh, sw), want_vec in cases:
+        k = wl.Kernel(wl.CLS_DWCONV_BIAS_RELU6, wl.ConvShape(n, c, h, w, c, 3, 3, sh, sw, 1, 1, wl.F32), 1, f"dw_{c}_{h}_{sh}{sw}")
+        scheds = [None, dw(2, 4, 8, 1, 2), dw(4, 2, 8, 2, 1, unroll=1), dw(1, 4, 16, 1, 4, vec=2), dw(2, 2, 16, 2, 2, stages=2),
+                  dw(7, 1, 64, 7, 1, vec=1)]
+        plan = api.tt_schedule_apply(scheds[1], k.cls, k.shape)
+        if plan.status == api.TT_OK:
+            assert plan.eff_vec_a == want_vec, (k.name, plan.eff_vec_a)
+            assert plan.tile_k == 8 * want_vec
+        P.check_kernel(k, scheds, seed=91)
+
+
 # ---- error behaviour --------------------------------------------------------------------------------
 def test_invalid_records_return_errors_and_write_nothing(api, P):
     import torch
