@@ -265,7 +265,7 @@ def test_invalid_records_return_errors_and_write_nothing(api, P):
     k2 = conv_kernel(k.cls, 1, 64, 14, 256, 3, 1)       # M = 196, N = 256
     dk2 = harness.device_kernel(k2, 6)
     dk2.output().fill_(7.0)
-    no_variant = mfma(api, k.cls, 128, 256, 32, 32, 64, 32)   # well-formed, applies, but is not compiled
+    no_variant = mfma(api, k.cls, 128, 256, 32, 128, 32, 32)  # well-formed, applies, but is not compiled
     assert api.tt_schedule_apply(no_variant, k2.cls, k2.shape).status == api.TT_OK
     assert dk2.run(no_variant) == api.TT_ERR_UNSUPPORTED
     torch.cuda.synchronize()
