@@ -97,14 +97,14 @@ def test_conv_bf16(api, P):
 
 @pytest.mark.parametrize("dt", [wl.F32, wl.BF16])
 @pytest.mark.parametrize("dims", [
-    (2, 16, 56, 32, 3, 1),    # rows of 56: full 16-byte vectors, one-element edge fix-ups
-    (3, 24, 14, 48, 3, 1),    # rows of 14: 2-element sub-vectors
-    (2, 8, 16, 32, 5, 1),     # 5x5, pad 2: edge shifts of up to two elements
-    (1, 4, 24, 16, 7, 1),     # 7x7, pad 3: edge shifts of up to three elements
-    (2, 32, 12, 32, 3, 1),    # rows of 12: 4-element sub-vectors
-    (5, 40, 7, 64, 3, 1),     # odd rows: element mode
-    (2, 48, 20, 96, 1, 1),    # pointwise: vectors span image rows (plane of 400 pixels)
-    (3, 36, 9, 64, 1, 1),     # pointwise with an odd plane (81 pixels): element mode across images
+    (2, 16, 56, 32, 3, 1),    # 16 channels: whole 16-byte items in both data types
+    (3, 24, 14, 48, 3, 1),    # 24 channels, small odd-sized maps
+    (2, 8, 16, 32, 5, 1),     # 5x5, pad 2: runs of 40 elements, two padded columns either side
+    (1, 4, 24, 16, 7, 1),     # 7x7, pad 3, 4 channels: whole items in fp32, partly real items in bf16
+    (2, 32, 12, 32, 3, 1),    # slices of 32 and 64 that end exactly on a pixel
+    (5, 40, 7, 64, 3, 1),     # 40 channels: slices straddle pixels and filter rows; 7 x 7 maps
+    (2, 48, 20, 96, 1, 1),    # unit-stride 1x1: the dense family
+    (3, 36, 9, 64, 1, 1),     # 1x1 with 36 channels: whole fp32 items (dense family), partly real bf16 items (gather)
 ])
 def test_conv_vector_gather_modes(api, P, dims, dt):
     n, c, hw, kk, f, st = dims
@@ -118,7 +118,7 @@ def test_conv_vector_gather_modes(api, P, dims, dt):
 
 
 def test_conv_padding_wider_than_filter_centre(api, P):
-    # pad larger than (filter - 1) / 2 makes the output wider than the input: vectors must not read outside a row
+    # pad larger than (filter - 1) / 2 makes the output wider than the input: whole filter columns fall outside
     for dt in (wl.F32, wl.BF16):
         k = conv_kernel(wl.CLS_CONV2D_ADD, 2, 8, 6, 16, 3, 1, dtype=dt, pad=2)   # 6x6 -> 8x8
         assert k.shape.wo == 8

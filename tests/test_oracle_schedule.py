@@ -100,8 +100,8 @@ def test_apply_derives_outer_extents_from_the_target():
     assert target["eff_split_k"] == 2 and target["k_iters"] == 9
     assert target["grid"] == 49 * 2 * 2 and target["block"] == 64 * 2
     assert target["workspace_bytes"] == 4 * 2 * 3136 * 64
-    # K-major activation tile 32 x (64 + 8) floats, row-major filter tile 32 x (32 + 4) floats, two stages
-    assert target["lds_bytes"] == 2 * (32 * 72 + 32 * 36) * 4
+    # row-major tiles padded by 16 bytes: activations 64 x (32 + 4) floats, filters 32 x (32 + 4) floats, two stages
+    assert target["lds_bytes"] == 2 * (64 * 36 + 32 * 36) * 4
 
 
 def test_factor_larger_than_loop_is_invalid_and_wrong_class_is_mismatch():
