@@ -333,6 +333,18 @@ int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out, int cap);
  */
 int tt_variant_info(int variant_id, int32_t out[10]);
 
+/*
+ * Which pre-tuned model to take the donor schedules from (Section 4.4.2, Eq. 1): for every candidate
+ * model T the score is the sum over the target's kernel classes c of P_c^2 * sqrt(|W_Tc|), where P_c is
+ * the share of class c in the target's untuned time and |W_Tc| the number of tuned kernels of that class
+ * model T offers.  class_cost[num_classes] holds the target's untuned time per class in any unit (it is
+ * normalised to shares here; all zero is TT_ERR_BAD_ARG); donor_class_count is [n_donors][num_classes],
+ * row-major, entries >= 0.  scores[n_donors] (may be NULL) receives every score; *best the index of the
+ * highest one, the lowest index winning ties, or -1 when n_donors is 0.  Host only.
+ */
+int tt_select_donor(const double *class_cost, int num_classes, const int32_t *donor_class_count, int n_donors,
+                    double *scores, int32_t *best);
+
 /* Pure selection step of the sweep on given times (host only; the rule tt_transfer_sweep uses). */
 int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t *pool_cls, int np, const double *pair_us,
                     const double *default_us, int allow_slower_than_default, tt_sweep_row *rows);

@@ -87,7 +87,7 @@ class tt_sweep_row(Structure):
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
            "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
-           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info")
+           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_select_donor")
 
 
 def _load():
@@ -124,6 +124,8 @@ def _load():
     lib.tt_variant_info.argtypes = [ctypes.c_int, POINTER(c_int32 * 10)]
     lib.tt_sweep_select.argtypes = [POINTER(c_int32), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
                                     POINTER(c_double), ctypes.c_int, POINTER(tt_sweep_row)]
+    lib.tt_select_donor.argtypes = [POINTER(c_double), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
+                                    POINTER(c_int32)]
     for name in EXPORTS:
         if name not in ("tt_status_name", "tt_last_error", "tt_debug_fast_div"):
             getattr(lib, name).restype = ctypes.c_int
@@ -215,6 +217,23 @@ def tt_sweep_select(kernel_cls, pool_cls, pair_us, default_us, allow_slower_than
 
 
 # ---- device helpers (torch is plumbing: memory and streams) -----------------------------------------
+def tt_select_donor(class_cost, donor_class_counts):
+    """Eq. 1: (index of the best candidate model, score of every candidate).
+
+    class_cost: sequence of the target's untuned time per class; donor_class_counts: one sequence of
+    per-class kernel counts per candidate model.
+    """
+    nc, nd = len(class_cost), len(donor_class_counts)
+    cost = (c_double * nc)(*[float(v) for v in class_cost])
+    flat = [int(v) for row in donor_class_counts for v in row]
+    assert len(flat) == nc * nd
+    counts = (c_int32 * max(len(flat), 1))(*flat)
+    scores = (c_double * max(nd, 1))()
+    best = c_int32(-1)
+    _check(lib.tt_select_donor(cost, nc, counts, nd, scores, byref(best)), "tt_select_donor")
+    return int(best.value), [float(scores[i]) for i in range(nd)]
+
+
 def _torch():
     import torch
     return torch

@@ -2,6 +2,7 @@
 // target kernel (paper Sections 4.1, 4.2), the host mirror of the index map,
 // the selection rule of the sweep (Section 4.3) and the enumerated space.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <vector>
 
@@ -477,6 +478,35 @@ extern "C" int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t 
         }
         row.best_us = row.chosen < 0 ? default_us[k] : best;
         rows[k] = row;
+    }
+    return TT_OK;
+}
+
+extern "C" int tt_select_donor(const double *class_cost, int num_classes, const int32_t *donor_class_count,
+                               int n_donors, double *scores, int32_t *best)
+{
+    if (!class_cost || num_classes < 1 || n_donors < 0 || !best || (n_donors && !donor_class_count)) return TT_ERR_BAD_ARG;
+    double total = 0.0;
+    for (int c = 0; c < num_classes; ++c) {
+        if (!(class_cost[c] >= 0.0)) return TT_ERR_BAD_ARG;
+        total += class_cost[c];
+    }
+    if (!(total > 0.0)) return TT_ERR_BAD_ARG;
+    *best = -1;
+    double best_score = 0.0;
+    for (int t = 0; t < n_donors; ++t) {
+        double score = 0.0;
+        for (int c = 0; c < num_classes; ++c) {
+            const int32_t count = donor_class_count[(size_t)t * num_classes + c];
+            if (count < 0) return TT_ERR_BAD_ARG;
+            const double share = class_cost[c] / total;
+            score += share * share * std::sqrt((double)count);
+        }
+        if (scores) scores[t] = score;
+        if (*best < 0 || score > best_score) { // strict '>': the lowest index wins ties
+            *best = t;
+            best_score = score;
+        }
     }
     return TT_OK;
 }

@@ -121,6 +121,23 @@ def load_pool(path: str) -> List[api.tt_schedule]:
     return pool
 
 
+# ---- which pool to transfer from (paper Section 4.4.2, Eq. 1) -------------------------------------------
+def choose_donor_pool(targets: Sequence[wl.Kernel], default_us: Sequence[float], pools: Dict[str, Sequence[api.tt_schedule]]):
+    """Rank candidate pools for a target network: (best name, {name: score}).
+
+    P_c is the share of class c in the target's time under the default schedules (each kernel's time
+    counted as often as the network uses it); |W_Tc| is the number of records of class c in a pool.
+    The arithmetic runs in the library (``tt_select_donor``).
+    """
+    cost = [0.0] * api.TT_NUM_CLASSES
+    for k, us in zip(targets, default_us):
+        cost[k.cls] += float(us) * k.use_count
+    names = list(pools)
+    counts = [[sum(1 for r in pools[n] if r.cls == c) for c in range(api.TT_NUM_CLASSES)] for n in names]
+    best, scores = api.tt_select_donor(cost, counts)
+    return (names[best] if best >= 0 else None), dict(zip(names, scores))
+
+
 # ---- workloads: target kernels and the donor kernels whose native optima form the pool -------------
 def workload(name: str):
     """(cfg index, target kernels, donor kernels) of a named configuration."""

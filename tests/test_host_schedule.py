@@ -161,3 +161,52 @@ def test_division_by_multiplication_is_exact():
                 continue
             assert api.lib.tt_debug_fast_div(n, d) == n // d, (n, d)
     assert api.lib.tt_debug_fast_div(5, 0) == -1 and api.lib.tt_debug_fast_div(2 ** 31, 3) == -1
+
+
+def test_donor_model_selection_matches_the_oracle_and_the_papers_choices():
+    """Eq. 1 in the library against the integer/float oracle and against Table 2's "Tuning Model" column."""
+    from test_oracle_schedule import parse_table2
+    models, _, _, _ = parse_table2()
+    classes = sorted({c for m in models.values() for c in m["cls"]})
+    for mid, m in models.items():
+        others = [t for t in models if t != mid]
+        cost = [m["cls"].get(c, (0, 0.0))[1] for c in classes]           # per cent of untuned time, any scale
+        counts = [[models[t]["cls"].get(c, (0, 0.0))[0] for c in classes] for t in others]
+        best, scores = api.tt_select_donor(cost, counts)
+        total = sum(cost)
+        want = [S.model_selection_score({c: p / total for c, p in zip(classes, cost)}, dict(zip(classes, row)))
+                for row in counts]
+        assert all(abs(a - b) <= 1e-12 * max(1.0, abs(b)) for a, b in zip(scores, want))
+        # the oracle's choice, ties to the lowest index; where the paper's percentages add to 100 it is Table 2's model
+        assert best == max(range(len(want)), key=lambda i: (want[i], -i))
+        assert others[best] == m["tuning"], (mid, others[best])
+    assert api.tt_select_donor([1.0, 2.0], []) == (-1, [])
+    with pytest.raises(api.TTError):
+        api.tt_select_donor([0.0, 0.0], [[1, 1]])
+    with pytest.raises(api.TTError):
+        api.tt_select_donor([1.0, 1.0], [[1, -1]])
+
+
+def test_choose_donor_pool_on_the_committed_sweep_outcomes():
+    """Eq. 1 end to end on stored data: ResNet18's default timings against the four committed pools."""
+    import json
+    from paper_2201_05587_amd import tune
+    tuned_dir = os.path.join(ROOT, "paper_2201_05587_amd", "tuned")
+    _, targets, _ = tune.workload("cfg2")
+    with open(os.path.join(tuned_dir, "cfg2.json")) as f:
+        by_name = {e["name"]: e for e in json.load(f)["kernels"]}
+    default_us = [by_name[k.name]["default_us"] for k in targets]
+    pools = {n: tune.load_pool(os.path.join(tuned_dir, f"{n}.pool")) for n in ("cfg3", "cfg4", "cfg2", "cfg5")}
+    best, scores = tune.choose_donor_pool(targets, default_us, pools)
+    # BERT-shaped records share only the classifier's class with a CNN; the conv pools win on their class-E records
+    assert scores["cfg3"] == min(scores.values()) and best in ("cfg2", "cfg5") and scores[best] == max(scores.values())
+    cost = {}
+    for k, us in zip(targets, default_us):
+        cost[k.cls] = cost.get(k.cls, 0.0) + us * k.use_count
+    total = sum(cost.values())
+    for n, pool in pools.items():
+        count = {}
+        for r in pool:
+            count[r.cls] = count.get(r.cls, 0) + 1
+        want = S.model_selection_score({c: v / total for c, v in cost.items()}, count)
+        assert abs(scores[n] - want) <= 1e-12 * max(1.0, want)
