@@ -35,12 +35,16 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq128_from_256",
+                                                           "seq256_from_128"])
     ap.add_argument("--sweep", action="store_true", help="run the sweeps and store their outcome")
     ap.add_argument("--retune-pool", action="store_true", help="also re-tune the donor kernels (the pool)")
     ap.add_argument("--donor-limit", type=int, default=0, help="use only the first N donor kernels")
     ap.add_argument("--level", type=int, default=1, help="size of the enumerated native space (0, 1, 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chain", action="store_true",
+                    help="cfg5 only: time the bottleneck blocks wired output-to-input against the same launches on "
+                         "independent tensors and against the sum of standalone times (prints its own JSON line)")
     return ap.parse_args()
 
 
@@ -99,6 +103,56 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
     return out
 
 
+def chain_leg(args, api, harness, tune, wl, targets, dks, transfer):
+    """Inter-kernel effects (paper Section 5.5): the bottleneck blocks 2..n of every ResNet-50 stage, chained."""
+    import torch
+    by_name = {k.name: i for i, k in enumerate(targets)}
+    chained, records, independent, standalone_us = [], [], [], 0.0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def single(i):
+        """The kernel on its private tensors, one launch per list entry."""
+        return api.DeviceKernel(targets[i].cls, targets[i].shape, dks[i].tensors, 1, targets[i].name, dks[i].ws.numel())
+
+    def standalone(i):
+        one = api.KernelList([single(i)], [transfer[i]])
+        one.run(3)
+        e0.record()
+        one.run(20)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / 20
+
+    for st, (wd, nb) in enumerate(zip([64, 128, 256, 512], [3, 4, 6, 3]), start=1):
+        cout = wd * 4
+        ir = by_name[f"r50_s{st}_reduce_{cout}_{wd}"]
+        ic = by_name["r50_s1_b1_3x3_s1" if st == 1 else f"r50_s{st}_3x3"]
+        ie = by_name[f"r50_s{st}_expand_{wd}_{cout}_res"]
+        blocks = nb - 1
+        cd, _, _ = harness.bottleneck_chain(targets[ir], targets[ic], targets[ie], blocks, wl.seed_for(5, 900 + st))
+        chained += cd
+        records += [transfer[ir], transfer[ic], transfer[ie]] * blocks
+        us = [standalone(i) for i in (ir, ic, ie)]
+        standalone_us += blocks * sum(us)
+        independent += [single(i) for _ in range(blocks) for i in (ir, ic, ie)]
+
+    def timed(klist):
+        klist.run(args.warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        klist.run(args.steps)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / args.steps
+
+    chain_us = timed(api.KernelList(chained, records))
+    indep_us = timed(api.KernelList(independent, records))
+    flops = sum(d_k.flops() for d_k in [targets[by_name[d.name.split("@")[0]]] for d in chained])
+    print(json.dumps({"chain": {"launches": len(chained), "gflop": flops / 1e9, "chained_us": chain_us,
+                                "same_launches_on_independent_tensors_us": indep_us,
+                                "sum_of_standalone_us": standalone_us,
+                                "chained_over_standalone": chain_us / standalone_us}}))
+
+
 def cpu_baseline_leg(wl, targets, budget_s=25.0):
     """The oracle, as it stands, on the host cores: each distinct kernel of the workload once, largest first,
     until the time budget is spent."""
@@ -153,6 +207,11 @@ def main():
     by_name = {e["name"]: e for e in tuned["kernels"]}
     transfer = [knobs_to_record(api, by_name[k.name]["transfer"]) for k in targets]
     native = [knobs_to_record(api, by_name[k.name]["native"]) for k in targets]
+
+    if args.chain:
+        assert args.workload == "cfg5", "--chain is defined for the ResNet-50-shaped configuration"
+        chain_leg(args, api, harness, tune, wl, targets, dks, transfer)
+        return
 
     # ---- timed region: K network-shaped passes under the transferred schedules ----
     klist = api.KernelList(dks, transfer)

@@ -59,3 +59,38 @@ def device_kernel(kernel: wl.Kernel, seed: int, inputs: dict | None = None, max_
     tensors[out_key] = torch.zeros(output_shape(kernel), dtype=api.torch_dtype(dt), device="cuda")
     return api.DeviceKernel(kernel.cls, kernel.shape, tensors, kernel.use_count, kernel.name,
                             max_workspace_bytes(kernel, max_split))
+
+
+def bottleneck_chain(k_reduce: wl.Kernel, k_conv: wl.Kernel, k_expand: wl.Kernel, blocks: int, seed: int):
+    """Residual bottleneck blocks wired output-to-input (paper Section 5.5: kernels run in their network context).
+
+    Each block is reduce (1x1) -> conv (3x3) -> expand (1x1 + residual + ReLU); the block's input is the
+    expand kernel's residual and the next block's input.  Every block reuses the same three filters
+    (timing and parity do not depend on the values).  Returns (device kernels in launch order, the
+    kernels they instantiate, host inputs: block input x0 and the three kernels' weights and biases).
+    """
+    import torch
+    sr, sc, se = k_reduce.shape, k_conv.shape, k_expand.shape
+    assert (sr.n, sr.ho, sr.wo, sr.k) == (sc.n, sc.h, sc.w, sc.c) and (sc.n, sc.ho, sc.wo, sc.k) == (se.n, se.h, se.w, se.c)
+    assert (se.n, se.ho, se.wo, se.k) == (sr.n, sr.h, sr.w, sr.c) and k_expand.cls == wl.CLS_CONV2D_BIAS_ADD_RELU
+    dt = sr.dtype
+    host = {"reduce": wl.make_inputs(k_reduce, seed), "conv": wl.make_inputs(k_conv, seed + 100),
+            "expand": wl.make_inputs(k_expand, seed + 200)}
+    dev = {name: {t: to_device(to_library_layout(k, t, v), dt) for t, v in inp.items() if t in ("w", "bias")}
+           for (name, inp), k in zip(host.items(), (k_reduce, k_conv, k_expand))}
+    x0 = host["reduce"]["x"]
+    tdt = api.torch_dtype(dt)
+    ping = to_device(to_library_layout(k_reduce, "x", x0), dt)
+    pong = torch.zeros_like(ping)
+    y1 = torch.zeros(output_shape(k_reduce), dtype=tdt, device="cuda")
+    y2 = torch.zeros(output_shape(k_conv), dtype=tdt, device="cuda")
+    dks, kinds = [], []
+    for b in range(blocks):
+        src, dst = (ping, pong) if b % 2 == 0 else (pong, ping)
+        wiring = ((k_reduce, "reduce", dict(x=src, y=y1)), (k_conv, "conv", dict(x=y1, y=y2)),
+                  (k_expand, "expand", dict(x=y2, res=src, y=dst)))
+        for k, name, io in wiring:
+            tensors = dict(dev[name], **io)
+            dks.append(api.DeviceKernel(k.cls, k.shape, tensors, 1, f"{k.name}@block{b}", max_workspace_bytes(k, 8)))
+            kinds.append(k)
+    return dks, kinds, dict(x0=x0, **{name: {t: inp[t] for t in ("w", "bias")} for name, inp in host.items()})

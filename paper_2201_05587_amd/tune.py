@@ -159,6 +159,11 @@ def workload(name: str):
         for i in range(10):
             donors += wl.synthetic_network(i, 32, wl.BF16, 30, exclude)
         return 5, targets, donors
+    # sequence-length transfer (paper Section 5.4): schedules tuned at one length applied at the other
+    if name == "seq128_from_256":
+        return 3, wl.bert_kernels(seq=128), wl.bert_kernels(seq=256)
+    if name == "seq256_from_128":
+        return 3, wl.bert_kernels(seq=256), wl.bert_kernels(seq=128)
     raise ValueError(f"unknown workload {name}")
 
 

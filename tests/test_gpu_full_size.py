@@ -136,3 +136,9 @@ def test_cfg3_bert_bf16_whole(index):
 @pytest.mark.parametrize("index", cases_of("cfg4"))
 def test_cfg4_mobilenetv2_fp32_whole(index):
     run_whole("cfg4", index)
+
+
+@pytest.mark.parametrize("index", cases_of("seq256_from_128"))
+def test_seq256_bert_bf16_whole(index):
+    """Targets at sequence length 256 under the records transferred from length 128 (Section 5.4)."""
+    run_whole("seq256_from_128", index)

@@ -249,6 +249,32 @@ def test_depthwise_channel_vectors_and_general_kernel(api, P):
         P.check_kernel(k, scheds, seed=91)
 
 
+# ---- kernels chained through shared tensors ---------------------------------------------------------
+def test_bottleneck_chain_matches_the_oracle_applied_in_sequence(api, P):
+    """Three kernels per block, the output tensor of one being the input of the next, two blocks."""
+    import torch
+    from oracle import ops as O
+    from paper_2201_05587_amd import harness
+    for dt in (wl.F32, wl.BF16):
+        kr = conv_kernel(wl.CLS_CONV2D_BIAS_RELU, 2, 64, 10, 32, 1, 1, dtype=dt)
+        kc = conv_kernel(wl.CLS_CONV2D_BIAS_RELU, 2, 32, 10, 32, 3, 1, dtype=dt)
+        ke = conv_kernel(wl.CLS_CONV2D_BIAS_ADD_RELU, 2, 32, 10, 64, 1, 1, dtype=dt)
+        dks, kinds, host = harness.bottleneck_chain(kr, kc, ke, 2, seed=17)
+        tk = 16 if dt == wl.F32 else 32
+        recs = [None, mfma(api, kc.cls, 32, 32, tk, 16, 16, 16, stages=3), mfma(api, ke.cls, 64, 32, tk, 32, 32, 32, split_k=2 if dt == wl.F32 else 1)] * 2
+        api.KernelList(dks, recs).run(1)
+        torch.cuda.synchronize()
+        x = host["x0"]
+        rnd = (lambda a: a) if dt == wl.F32 else O.round_to_bf16   # each kernel stores bf16 outputs
+        for _ in range(2):
+            y1 = rnd(O.conv2d(x, host["reduce"]["w"], host["reduce"]["bias"], None, (1, 1), (0, 0), O.ACT_RELU))
+            y2 = rnd(O.conv2d(y1, host["conv"]["w"], host["conv"]["bias"], None, (1, 1), (1, 1), O.ACT_RELU))
+            x = rnd(O.conv2d(y2, host["expand"]["w"], host["expand"]["bias"], x, (1, 1), (0, 0), O.ACT_RELU))
+        got = harness.output_in_definition_order(ke, dks[-1].output()).float().cpu().numpy()
+        # six kernels deep: the bf16 roundings of the intermediate tensors can differ by one unit in the last place
+        P.assert_close(got, x, dt, f"chain {dt}")
+
+
 # ---- error behaviour --------------------------------------------------------------------------------
 def test_invalid_records_return_errors_and_write_nothing(api, P):
     import torch
