@@ -36,14 +36,9 @@
  *     returns the error and writes nothing: falling back to the default schedule
  *     is the sweep's decision (Section 4.3), not the operator's.  A NULL schedule
  *     means "the default schedule of this kernel";
- *   - a record that splits the reduction needs the caller's workspace `ws`; its size for a
- *     given (schedule, shape) is tt_plan.workspace_bytes.  Too small a workspace is
- *     TT_ERR_WORKSPACE.  The workspace starts with one arrival counter per 16 x 16 output tile
- *     (256-byte rounded; the same place for every record of a kernel), followed by one fp32
- *     partial-sum matrix per split.  The counters must be ZERO when an operator call starts and
- *     every call leaves them zero: call tt_workspace_prepare once after allocating a workspace, and
- *     again before using it for a kernel of another shape.  Calls that share a workspace must not
- *     overlap in time.
+ *   - split-K partial sums live in the caller's workspace `ws`; its size for a
+ *     given (schedule, shape) is tt_plan.workspace_bytes.  Too small a workspace
+ *     is TT_ERR_WORKSPACE.
  */
 #ifndef TT_H
 #define TT_H
@@ -216,13 +211,6 @@ int tt_schedule_apply(const tt_schedule *sched, int cls, const void *shape, int 
  * TT_SK_DIRECT (TT_ERR_BAD_ARG).
  */
 int tt_plan_tile(const tt_plan *plan, int64_t wg, int32_t out[8]);
-
-/*
- * Zero a split-K workspace (its arrival counters must be zero before the first operator call that uses
- * it; see the conventions above).  Enqueues a fill kernel on `stream`; ws is a device pointer, 16-byte
- * aligned.  ws_bytes == 0 is a no-op.
- */
-int tt_workspace_prepare(void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Run the device's own index decode for every workgroup of the plan and write

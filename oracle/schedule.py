@@ -242,19 +242,6 @@ def staged_tile_bytes(cls: int, shape: dict, rec: dict) -> int:
     return row_major(tm) + k_major(tn)
 
 
-def tile_counter_bytes(batch: int, M: int, N: int) -> int:
-    """Head of a split-K workspace: one arrival counter per output tile of the finest tiling (16 x 16), so that
-    every plan of a kernel finds its counters in the same place; rounded up to 256 bytes."""
-    return ceil_div(4 * batch * ceil_div(M, 16) * ceil_div(N, 16), 256) * 256
-
-
-def split_workspace_bytes(batch: int, M: int, N: int, eff_split_k: int) -> int:
-    """Counters, then one fp32 partial-sum matrix per split; nothing when the reduction is not split."""
-    if eff_split_k <= 1:
-        return 0
-    return tile_counter_bytes(batch, M, N) + 4 * eff_split_k * batch * M * N
-
-
 def _blank_plan():
     return {f: 0 for f in PLAN_FIELDS}
 
@@ -446,7 +433,7 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_GRID)
     plan.update(eff_split_k=eff_split_k, k_iters=k_iters, slabs=slabs, eff_vec_a=eva, eff_vec_b=evb,
                 eff_vec_c=evc, eff_unroll=min(rec["unroll"], tk // gran), grid=grid, block=64 * waves,
-                lds_bytes=lds, workspace_bytes=split_workspace_bytes(batch, M, N, eff_split_k))
+                lds_bytes=lds, workspace_bytes=(4 * eff_split_k * batch * M * N) if eff_split_k > 1 else 0)
     return plan
 
 

@@ -86,7 +86,7 @@ class tt_sweep_row(Structure):
 
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
-           "tt_debug_tile_map", "tt_debug_fast_div", "tt_workspace_prepare", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
+           "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
            "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_select_donor")
 
 
@@ -106,7 +106,6 @@ def _load():
     lib.tt_schedule_apply.argtypes = [POINTER(tt_schedule), ctypes.c_int, c_void_p, ctypes.c_int, POINTER(tt_plan)]
     lib.tt_plan_tile.argtypes = [POINTER(tt_plan), c_int64, POINTER(c_int32 * 8)]
     lib.tt_debug_tile_map.argtypes = [POINTER(tt_plan), c_void_p, c_void_p]
-    lib.tt_workspace_prepare.argtypes = [c_void_p, c_size_t, c_void_p]
     lib.tt_conv2d_bias_relu.argtypes = [c_void_p] * 5 + [POINTER(tt_conv_shape), ctypes.c_int, POINTER(tt_schedule),
                                                          c_void_p, c_size_t, c_void_p]
     lib.tt_dense_bias_relu.argtypes = [c_void_p] * 4 + [POINTER(tt_gemm_shape), ctypes.c_int, POINTER(tt_schedule),
@@ -264,9 +263,7 @@ def _ws_for(sched, cls, shape, ws):
     need = workspace_bytes(sched, cls, shape)
     if need == 0:
         return None
-    ws = _torch().empty(need, dtype=_torch().uint8, device="cuda")
-    _check(lib.tt_workspace_prepare(ws.data_ptr(), ws.numel(), _stream()), "tt_workspace_prepare")
-    return ws
+    return _torch().empty(need, dtype=_torch().uint8, device="cuda")
 
 
 def tt_conv2d_bias_relu(x, w, bias, residual, shape, cls, sched=None, ws=None, y=None):
@@ -339,7 +336,6 @@ class DeviceKernel:
         self.cshape = to_c_shape(shape)
         self.tensors = tensors  # dict name -> device tensor (kept alive here)
         self.ws = torch.empty(max(int(ws_bytes), 16), dtype=torch.uint8, device="cuda")
-        _check(lib.tt_workspace_prepare(self.ws.data_ptr(), self.ws.numel(), _stream()), "tt_workspace_prepare")
         if cls in CONV_CLASSES:
             order = ("x", "w", "bias", "res", "y")
         elif cls in DENSE_CLASSES or cls == TT_DWCONV_BIAS_RELU6:

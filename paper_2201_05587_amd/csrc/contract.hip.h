@@ -474,58 +474,6 @@ template <int TM, int WM, int WN, int MF> struct TileOut {
     }
 };
 
-// Bias, residual, activation, down-conversion and store of the 8 consecutive outputs (m, first .. first + 7)
-// whose sums are `lo` and `hi`, in groups of vc columns that are all inside or all outside the matrix.
-template <int DT>
-__device__ __forceinline__ void finish_outputs(const ContractArgs &g, const f32x4 &lo, const f32x4 &hi, int64_t row_base,
-                                               int first, int vc)
-{
-    const float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    for (int e0 = 0; e0 < 8; e0 += vc) {
-        const int n = first + e0;
-        if (n >= g.N) break;
-        const int64_t idx = row_base + n;
-        if (vc == 8 && DT == TT_BF16) {
-            u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
-            if (g.has_res) resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
-            if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
-            u32x4 outv;
-#pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
-                float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) + __uint_as_float(resv[h] & 0xffff0000u);
-                outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
-                          ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
-            }
-            *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
-        } else if (vc >= 4 && DT == TT_F32) {
-#pragma unroll
-            for (int q4 = 0; q4 < 2; ++q4) {
-                if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
-                f32x4 r = q4 == 0 ? lo : hi;
-                const int64_t at = idx + (q4 * 4 - e0);
-                f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (g.has_bias) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
-                if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
-                *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
-            }
-        } else {
-            for (int e = 0; e < vc; ++e) {
-                float a = val[e0 + e];
-                if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
-                if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
-                store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
-            }
-        }
-    }
-}
-
-// With a split reduction every workgroup first stores its partial sums (fp32, the same vector pattern)
-// into its own matrix of the workspace and then counts itself in on the tile's arrival counter.  The
-// workgroup that arrives last re-reads all partial matrices of the tile IN SPLIT ORDER - so the result
-// does not depend on which one that was - applies the epilogue, and sets the counter back to zero.
 template <int DT, int TM, int WM, int WN, int MF, typename Acc>
 __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
                                            unsigned char *smem, int wave, int lane)
@@ -533,11 +481,11 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
     using T = TileOut<TM, WM, WN, MF>;
     constexpr int NI = T::NI, NJ = T::NJ, ACC = T::ACC, ESTRIDE = T::ESTRIDE, CG = T::CG, PASSES = T::PASSES;
     const int lane_r = lane % MF, lane_g = lane / MF;
+    const int bidx = tc.hi;
     float *stage = reinterpret_cast<float *>(smem) + wave * (MF * ESTRIDE);
-    const int splits = g.map.eff_split_k;
-    const bool partial = splits > 1;
-    const int64_t mn = (int64_t)g.M * g.N, slab = (int64_t)g.batch * mn;
-    float *ws = g.ws + (int64_t)tc.lo * slab;
+    const bool partial = g.map.eff_split_k > 1;
+    const int64_t mn = (int64_t)g.M * g.N;
+    float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
     const int vc = g.eff_vec_c; // consecutive outputs of a row that are all inside or all outside the matrix
     const int cg = lane % CG;
     const int first = tc.n0 + T::col(wave, lane);
@@ -563,64 +511,65 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
             const int row_l = ps * T::ROWS_PER_PASS + lane / CG;
             const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8);
             const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
+            float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             const int m = tc.m0 + T::row(wave, lane, i, ps);
             if (m >= g.M) continue;
-            const int64_t row_base = (int64_t)tc.hi * mn + (int64_t)m * g.N;
-            if (!partial) {
-                finish_outputs<DT>(g, lo, hi, row_base, first, vc);
-                continue;
-            }
-            const float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            // groups of vc consecutive columns
             for (int e0 = 0; e0 < 8; e0 += vc) {
                 const int n = first + e0;
                 if (n >= g.N) break;
-                float *at = ws + row_base + n;
-                if (vc == 8) {
-                    *reinterpret_cast<f32x4 *>(at) = lo;
-                    *reinterpret_cast<f32x4 *>(at + 4) = hi;
-                } else if (vc == 4) {
-                    *reinterpret_cast<f32x4 *>(at) = e0 == 0 ? lo : hi;
+                const int64_t idx = (int64_t)bidx * mn + (int64_t)m * g.N + n;
+                if (partial) {
+                    if (vc == 8) {
+                        *reinterpret_cast<f32x4 *>(ws + idx) = lo;
+                        *reinterpret_cast<f32x4 *>(ws + idx + 4) = hi;
+                    } else if (vc == 4) {
+                        *reinterpret_cast<f32x4 *>(ws + idx) = e0 == 0 ? lo : hi;
+                    } else {
+                        for (int e = 0; e < vc; ++e) ws[idx + e] = val[e0 + e];
+                    }
+                    continue;
+                }
+                if (vc == 8 && DT == TT_BF16) {
+                    u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
+                    if (g.has_res)
+                        resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
+                    if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
+                    u32x4 outv;
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
+                        float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) +
+                                  __uint_as_float(resv[h] & 0xffff0000u);
+                        outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
+                                  ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
+                    }
+                    *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
+                } else if (vc >= 4 && DT == TT_F32) {
+#pragma unroll
+                    for (int q4 = 0; q4 < 2; ++q4) {
+                        if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
+                        f32x4 r = q4 == 0 ? lo : hi;
+                        const int64_t at = idx + (q4 * 4 - e0);
+                        f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (g.has_bias)
+                            add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
+                        if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
+                    }
                 } else {
-                    for (int e = 0; e < vc; ++e) at[e] = val[e0 + e];
+                    for (int e = 0; e < vc; ++e) {
+                        float a = val[e0 + e];
+                        if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
+                        if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
+                        store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
+                    }
                 }
             }
         }
     }
-    if (!partial) return;
-
-    // publish the partial sums, then count this workgroup in
-    __threadfence();
-    __syncthreads();
-    uint32_t *flag = reinterpret_cast<uint32_t *>(smem);
-    const int tile_id = (tc.hi * g.map.tiles_m + tc.m0 / g.map.tile_m) * g.map.tiles_n + tc.n0 / g.map.tile_n;
-    if (threadIdx.x == 0) *flag = atomicAdd(g.sem + tile_id, 1u);
-    __syncthreads();
-    if (*flag != (uint32_t)(splits - 1)) return; // not the last one: done
-    __threadfence(); // the other workgroups' partial sums are visible from here on
-
-    for (int i = 0; i < NI; ++i)
-        for (int ps = 0; ps < PASSES; ++ps) {
-            if (!T::pass_live(lane, ps)) continue;
-            const int m = tc.m0 + T::row(wave, lane, i, ps);
-            if (m >= g.M) continue;
-            const int64_t row_base = (int64_t)tc.hi * mn + (int64_t)m * g.N;
-            f32x4 lo = {0.0f, 0.0f, 0.0f, 0.0f}, hi = {0.0f, 0.0f, 0.0f, 0.0f};
-            for (int z = 0; z < splits; ++z) {
-                const float *src = g.ws + (int64_t)z * slab + row_base + first;
-                if (vc >= 4) {
-                    if (first < g.N) lo += *reinterpret_cast<const f32x4 *>(src);
-                    if (first + 4 < g.N) hi += *reinterpret_cast<const f32x4 *>(src + 4);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (first + e < g.N) lo[e] += src[e];
-                        if (first + 4 + e < g.N) hi[e] += src[4 + e];
-                    }
-                }
-            }
-            finish_outputs<DT>(g, lo, hi, row_base, first, vc);
-        }
-    if (threadIdx.x == 0) g.sem[tile_id] = 0u; // every workgroup of the tile has arrived: ready for the next launch
 }
 
 // LDS bytes of one pipeline stage: the A tile followed by the B tile.

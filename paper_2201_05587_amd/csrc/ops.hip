@@ -50,7 +50,6 @@ void fill_common(ContractArgs &g, const tt_plan &plan, const tt_schedule *sched,
     g.M = plan.M;
     g.N = plan.N;
     g.K = plan.K;
-    g.sem = nullptr;
     g.eff_vec_a = plan.eff_vec_a;
     g.eff_vec_b = plan.eff_vec_b;
     g.eff_vec_c = plan.eff_vec_c;
@@ -59,14 +58,6 @@ void fill_common(ContractArgs &g, const tt_plan &plan, const tt_schedule *sched,
     g.act = act_of_class(cls);
     g.dtype = dtype;
     (void)sched;
-}
-
-// Split-K workspace: arrival counters first, the partial-sum matrices behind them.
-void set_workspace(ContractArgs &g, const tt_plan &plan, void *ws)
-{
-    g.sem = static_cast<uint32_t *>(ws);
-    g.ws = ws ? reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + tile_counter_bytes(plan.batch, plan.M, plan.N))
-              : nullptr;
 }
 
 int run_contraction(ContractArgs &g, const tt_plan &plan, int family, void *stream)
@@ -78,8 +69,10 @@ int run_contraction(ContractArgs &g, const tt_plan &plan, int family, void *stre
         return launch_gemv(g, plan, stream);
     case TT_SK_MFMA: {
         if (plan.variant_id < 0 || plan.variant_id >= kNumVariants) return TT_ERR_UNSUPPORTED;
-        // a split reduction is summed by the last workgroup of each output tile, inside the same launch
-        return kVariants[plan.variant_id].launch(g, plan.grid, plan.lds_bytes, stream);
+        const int rc = kVariants[plan.variant_id].launch(g, plan.grid, plan.lds_bytes, stream);
+        if (rc != TT_OK) return rc;
+        if (plan.eff_split_k > 1) return launch_splitk_reduce(g, family, stream);
+        return TT_OK;
     }
     default:
         return TT_ERR_UNSUPPORTED;
@@ -114,7 +107,7 @@ extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bia
     g.bias = bias;
     g.res = residual;
     g.out = y;
-    set_workspace(g, plan, ws);
+    g.ws = static_cast<float *>(ws);
     g.has_bias = bias != nullptr;
     g.has_res = residual != nullptr;
     g.C = shape->c;
@@ -156,7 +149,7 @@ static int gemm_entry(const void *a, const void *b, const void *bias, void *c, c
     g.b = b;
     g.bias = bias;
     g.out = c;
-    set_workspace(g, plan, ws);
+    g.ws = static_cast<float *>(ws);
     g.has_bias = bias != nullptr;
     g.Ho = g.Wo = 1;
     return run_contraction(g, plan, family_of(cls, shape->trans_b), stream);
@@ -211,13 +204,6 @@ extern "C" int tt_dwconv(const void *x, const void *w, const void *bias, void *y
     g.x_bytes = x_bytes < (1ll << 31) ? (uint32_t)x_bytes : 0u;
     if (plan.sketch == TT_SK_DIRECT) return launch_dw_direct(g, plan.grid, stream);
     return launch_dwconv(g, plan, stream);
-}
-
-extern "C" int tt_workspace_prepare(void *ws, size_t ws_bytes, void *stream)
-{
-    if ((!ws && ws_bytes) || !aligned16(ws)) return TT_ERR_BAD_ARG;
-    if (!ws_bytes) return TT_OK;
-    return launch_fill_zero(ws, ws_bytes, stream);
 }
 
 extern "C" int tt_debug_tile_map(const tt_plan *plan, int32_t *out_dev, void *stream)

@@ -408,9 +408,7 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
     p.grid = (int)grid;
     p.lds_bytes = (int)lds;
-    // arrival counters (one per tile of the finest tiling, so every plan of a kernel finds them in the same
-    // place), then one fp32 partial-sum matrix per split
-    p.workspace_bytes = p.eff_split_k > 1 ? tile_counter_bytes(e.batch, e.M, e.N) + 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
+    p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
     p.variant_id = find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode,
                                 p.stages >= 3 ? 1 : 0);
     *plan = p;

@@ -1,10 +1,8 @@
 // Kernels that do not use the matrix cores: the one-thread-per-output "direct"
-// sketch (the unscheduled loop nest, always valid), the zero fill of a split-K
-// workspace, the wave-reduction GEMV sketch for small-M dense kernels,
+// sketch (the unscheduled loop nest, always valid), the split-K reduction with
+// the fused epilogue, the wave-reduction GEMV sketch for small-M dense kernels,
 // the depthwise 3x3 tile kernel, and the index-map dump.
 #include <hip/hip_runtime.h>
-
-#include <algorithm>
 
 #include "contract.hip.h"
 #include "tt_internal.h"
@@ -63,12 +61,18 @@ template <int DT, int FAM> __global__ void __launch_bounds__(256) direct_kernel(
     store_from_float<DT>(g.out, idx, apply_act(acc, g.act));
 }
 
-// ---- zero fill (workspace preparation; a kernel so that callers may capture it in a graph) -------------------
-__global__ void __launch_bounds__(256) fill_zero_kernel(uint32_t *p, size_t words, unsigned char *tail, int tail_bytes)
+// ---- split-K: sum the partial tiles in split order, then the fused epilogue -----------------------
+template <int DT> __global__ void __launch_bounds__(256) splitk_reduce_kernel(const ContractArgs g)
 {
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += stride) p[i] = 0u;
-    if (blockIdx.x == 0 && (int)threadIdx.x < tail_bytes) tail[threadIdx.x] = 0;
+    const int64_t total = (int64_t)g.batch * g.M * g.N;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    float acc = 0.0f;
+    for (int z = 0; z < g.map.eff_split_k; ++z) acc += g.ws[(int64_t)z * total + idx];
+    const int n = (int)(idx % g.N);
+    if (g.has_bias) acc += load_as_float<DT>(g.bias, n);
+    if (g.has_res) acc += load_as_float<DT>(g.res, idx);
+    store_from_float<DT>(g.out, idx, apply_act(acc, g.act));
 }
 
 // ---- GEMV sketch: a wave owns WN outputs of TMR rows; lanes split K; butterfly reduction ---------
@@ -347,12 +351,16 @@ int launch_direct(const ContractArgs &args, int family, int grid, void *stream)
                                 : launch_direct_dt<TT_BF16>(args, family, grid, s);
 }
 
-int launch_fill_zero(void *ptr, size_t bytes, void *stream)
+int launch_splitk_reduce(const ContractArgs &args, int family, void *stream)
 {
-    const size_t words = bytes / 4;
-    const int grid = (int)std::min<size_t>((words + 255) / 256 + 1, 4096);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<uint32_t *>(ptr), words, static_cast<unsigned char *>(ptr) + words * 4, (int)(bytes % 4));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t total = (int64_t)args.batch * args.M * args.N;
+    const int grid = (int)((total + 255) / 256);
+    (void)family; // every family writes a row-major [M][N] output
+    if (args.dtype == TT_F32)
+        hipLaunchKernelGGL((splitk_reduce_kernel<TT_F32>), dim3(grid), dim3(256), 0, s, args);
+    else
+        hipLaunchKernelGGL((splitk_reduce_kernel<TT_BF16>), dim3(grid), dim3(256), 0, s, args);
     return launched();
 }
 

@@ -126,14 +126,6 @@ inline FastDiv make_fastdiv(uint32_t d)
 }
 TT_HD uint32_t fast_div(uint32_t n, const FastDiv &f) { return (uint32_t)((((uint64_t)n * f.magic) >> 31) >> f.shift); }
 
-// Bytes at the head of a split-K workspace that hold the per-tile arrival counters: one 32-bit counter per
-// 16 x 16 output tile (the finest tiling), rounded up to 256 bytes.  The same for every plan of a kernel.
-inline int64_t tile_counter_bytes(int64_t batch, int64_t M, int64_t N)
-{
-    const int64_t raw = 4 * batch * ((M + 15) / 16) * ((N + 15) / 16);
-    return (raw + 255) / 256 * 256;
-}
-
 // Operand families of the matrix-core contraction kernel.
 enum Family {
     FAM_CONV = 0,    // A = NHWC activations gathered as an implicit GEMM, B = KRSC filters ([N][K])
@@ -145,8 +137,7 @@ enum Family {
 struct ContractArgs {
     const void *a, *b, *bias, *res;
     void *out;
-    float *ws;      // split-K: first partial-sum matrix (behind the counters)
-    uint32_t *sem;  // split-K: per-tile arrival counters, zero between launches
+    float *ws;
     TileMap map;
     int32_t batch, M, N, K;
     // convolution geometry (FAM_CONV).  The reduction index is k = r * runp + j: filter row r and
@@ -184,7 +175,7 @@ int family_of(int cls, int trans_b);
 
 // launchers of the non-matrix-core kernels (simple_kernels.hip)
 int launch_direct(const ContractArgs &args, int family, int grid, void *stream);
-int launch_fill_zero(void *ptr, size_t bytes, void *stream);
+int launch_splitk_reduce(const ContractArgs &args, int family, void *stream);
 int launch_gemv(const ContractArgs &args, const tt_plan &plan, void *stream);
 int launch_dwconv(const DwArgs &args, const tt_plan &plan, void *stream);
 int launch_dw_direct(const DwArgs &args, int grid, void *stream);

@@ -43,12 +43,10 @@ def output_shape(kernel: wl.Kernel):
 
 
 def max_workspace_bytes(kernel: wl.Kernel, max_split: int = 32) -> int:
-    """An upper bound of tt_plan.workspace_bytes over every record with split_k <= max_split."""
     b, m, n, _ = kernel.gemm_extents()
     if kernel.cls == wl.CLS_DWCONV_BIAS_RELU6:
         return 0
-    counters = 4 * b * ((m + 15) // 16) * ((n + 15) // 16) + 256
-    return counters + 4 * max_split * b * m * n
+    return 4 * max_split * b * m * n
 
 
 def device_kernel(kernel: wl.Kernel, seed: int, inputs: dict | None = None, max_split: int = 32) -> api.DeviceKernel:

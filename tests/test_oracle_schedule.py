@@ -99,8 +99,7 @@ def test_apply_derives_outer_extents_from_the_target():
     assert donor["tail_m"] == 784 - 12 * 64 and target["tail_m"] == 64
     assert target["eff_split_k"] == 2 and target["k_iters"] == 9
     assert target["grid"] == 49 * 2 * 2 and target["block"] == 64 * 2
-    # one arrival counter per 16 x 16 output tile (196 x 4 of them, rounded up to 256 bytes), then two fp32 matrices
-    assert target["workspace_bytes"] == 3328 + 4 * 2 * 3136 * 64
+    assert target["workspace_bytes"] == 4 * 2 * 3136 * 64
     # row-major tiles padded by 16 bytes: activations 64 x (32 + 4) floats, filters 32 x (32 + 4) floats, two stages
     assert target["lds_bytes"] == 2 * (64 * 36 + 32 * 36) * 4
 
