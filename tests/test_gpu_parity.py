@@ -249,6 +249,26 @@ def test_depthwise_channel_vectors_and_general_kernel(api, P):
         P.check_kernel(k, scheds, seed=91)
 
 
+# ---- split reduction ---------------------------------------------------------------------------------
+def test_split_k_is_deterministic(api, P):
+    """Partial sums are added in split order by the reduce kernel: bits do not depend on scheduling."""
+    from paper_2201_05587_amd import harness
+    for dt in (wl.F32, wl.BF16):
+        tk = 16 if dt == wl.F32 else 32
+        k = conv_kernel(wl.CLS_CONV2D_BIAS_ADD_RELU, 2, 64, 14, 96, 3, 1, dtype=dt)     # K = 576, ragged N tiles
+        recs = [mfma(api, k.cls, 32, 32, tk, 16, 16, 16, split_k=6), mfma(api, k.cls, 64, 64, tk, 32, 32, 16, split_k=6, stages=3),
+                mfma(api, k.cls, 64, 64, tk, 32, 16, 16, split_k=6, order=4)]
+        ref, outs = P.check_kernel(k, recs, seed=5)
+        # the same (tile_k, split_k, matrix-core block) gives the same summation order whatever the tile, pipeline or raster
+        np.testing.assert_array_equal(outs[0], outs[1])
+        np.testing.assert_array_equal(outs[0], outs[2])
+        dk = harness.device_kernel(k, 5)
+        first = P.run_gpu(k, dk, recs[1])
+        for _ in range(5):
+            np.testing.assert_array_equal(P.run_gpu(k, dk, recs[1]), first)
+        np.testing.assert_array_equal(first, outs[1])
+
+
 # ---- kernels chained through shared tensors ---------------------------------------------------------
 def test_bottleneck_chain_matches_the_oracle_applied_in_sequence(api, P):
     """Three kernels per block, the output tensor of one being the input of the next, two blocks."""
