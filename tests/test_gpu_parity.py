@@ -328,6 +328,35 @@ def test_invalid_records_return_errors_and_write_nothing(api, P):
     assert rc == api.TT_ERR_BAD_ARG
 
 
+def test_degenerate_shapes_fall_back_to_the_direct_or_gemv_sketch(api, P):
+    """Extents too small for a matrix-core tile: the default record is the unscheduled loop nest (or GEMV)."""
+    cases = [wl.Kernel(wl.CLS_CONV2D_BIAS_RELU, wl.ConvShape(1, 1, 1, 1, 1, 1, 1, 1, 1, 0, 0, wl.F32), 1, "conv_1x1x1"),
+             wl.Kernel(wl.CLS_CONV2D_BIAS_ADD_RELU, wl.ConvShape(2, 3, 5, 4, 7, 3, 3, 2, 1, 1, 2, wl.BF16), 1, "conv_tiny_bf16"),
+             wl.Kernel(wl.CLS_DENSE_BIAS_GELU, wl.GemmShape(1, 1, 1, 1, 1, wl.F32), 1, "dense_1x1x1"),
+             wl.Kernel(wl.CLS_DENSE_ADD, wl.GemmShape(1, 3, 5, 7, 1, wl.BF16), 1, "dense_tiny_bf16"),
+             wl.Kernel(wl.CLS_BATCH_MATMUL, wl.GemmShape(3, 2, 3, 4, 0, wl.F32), 1, "bmm_tiny_nn"),
+             wl.Kernel(wl.CLS_DWCONV_BIAS_RELU6, wl.ConvShape(1, 3, 4, 5, 3, 3, 3, 1, 1, 1, 1, wl.F32), 1, "dw_tiny")]
+    for k in cases:
+        rec = api.tt_schedule_default(k.cls, k.shape)
+        assert rec.sketch in (api.TT_SK_DIRECT, api.TT_SK_GEMV), (k.name, rec)
+        P.check_kernel(k, [None], seed=3)
+
+
+def test_tensors_of_two_gib_are_refused_by_the_matrix_core_conv_not_launched(api, P):
+    """The conv kernels address tensors with 32-bit byte offsets: larger ones are TT_ERR_UNSUPPORTED."""
+    import ctypes
+    import torch
+    dummy = torch.zeros(64, device="cuda")
+    huge = api.to_c_shape(wl.ConvShape(64, 256, 512, 512, 64, 3, 3, 1, 1, 1, 1, wl.BF16))   # 8 GiB of activations
+    rec = mfma(api, wl.CLS_CONV2D_BIAS_RELU, 64, 64, 32, 32, 32, 16)
+    assert api.tt_schedule_apply(rec, wl.CLS_CONV2D_BIAS_RELU, huge).status == api.TT_OK
+    p = dummy.data_ptr()
+    rc = api.lib.tt_conv2d_bias_relu(p, p, p, None, p, ctypes.byref(huge), wl.CLS_CONV2D_BIAS_RELU, ctypes.byref(rec), None, 0, None)
+    assert rc == api.TT_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert float(dummy.abs().sum()) == 0.0
+
+
 # ---- sweep ------------------------------------------------------------------------------------------
 def test_transfer_sweep_on_cfg1(api, P):
     from paper_2201_05587_amd import harness
