@@ -572,6 +572,17 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
     }
 }
 
+// How many consecutive steps of a slice have their fragment reads issued together, ahead of the first
+// product: the largest power of two dividing `steps` whose fragments (4 registers each) fit `budget`
+// registers.  A wave then pays the LDS latency once per group instead of once per step, which the few
+// waves of a workgroup that owns a CU alone cannot hide otherwise.
+constexpr int steps_per_group(int fragments_per_step, int steps, int budget = 64)
+{
+    int g = 1;
+    while (g * 2 <= steps && steps % (g * 2) == 0 && fragments_per_step * 4 * g * 2 <= budget) g *= 2;
+    return g;
+}
+
 // LDS bytes of one pipeline stage: the A tile followed by the B tile.
 template <int DT, int FAM, int TM, int TN, int TK, int MF> struct StageLayout {
     using E = typename ElemOf<DT>::type;
@@ -694,6 +705,33 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
             for (int j = 0; j < NJ; ++j) M::run(acc[i][j], rf[i], cf[j]);
     };
 
+    // a slice's global loads are held in registers here as well: a smaller budget, and none to spare
+    // for the workgroups of 16 waves (128 registers per lane)
+    constexpr int GROUP = steps_per_group(NI + NJ, NKS, THREADS > 512 ? 16 : 48);
+    auto k_group = [&](const unsigned char *sr, const unsigned char *sc, int ks0) {
+        u32x4 rf[GROUP][NI], cf[GROUP][NJ];
+#pragma unroll
+        for (int s = 0; s < GROUP; ++s) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                rf[s][i] = *reinterpret_cast<const u32x4 *>(sr + r_off + i * MF * ROWB + (ks0 + s) * KS * ES);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                if constexpr (B_KMAJOR)
+                    cf[s][j] = kmajor_fragment<DT, MF, L::LEN_B>(sc, wc * WN + j * MF, (ks0 + s) * KS, lane);
+                else
+                    cf[s][j] = *reinterpret_cast<const u32x4 *>(sc + c_off + j * MF * ROWB + (ks0 + s) * KS * ES);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0); // keep the reads ahead of the products
+#pragma unroll
+        for (int s = 0; s < GROUP; ++s)
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) M::run(acc[i][j], rf[s][i], cf[s][j]);
+    };
+
     fetch(0);
     stash(0, 0);
     __syncthreads();
@@ -708,7 +746,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
             const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
             if constexpr (decltype(unroll_steps)::value) {
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+                for (int ks = 0; ks < NKS; ks += GROUP) k_group(sa, sb, ks);
             } else {
 #pragma unroll 1
                 for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
@@ -878,6 +916,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     using BRows = AsyncRows<DT, TN, TK, THREADS>;
     constexpr int LPS = ARows::NL + BRows::NL; // loads per slice and thread
     static_assert(2 * LPS < 64, "too many loads in flight for the counter");
+    constexpr int GROUP = steps_per_group(NI + NJ, NKS);
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = lds_address(smem);
@@ -945,6 +984,26 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
             for (int j = 0; j < NJ; ++j) M::run(acc[i][j], rf[i], cf[j]);
     };
 
+    // GROUP consecutive steps with all their fragment reads issued before the first product
+    auto k_group = [&](const unsigned char *sa, const unsigned char *sb, int ks0) {
+        u32x4 rf[GROUP][NI], cf[GROUP][NJ];
+#pragma unroll
+        for (int s = 0; s < GROUP; ++s) {
+            const int at = (((ks0 + s) * LG + lane_g) ^ swz) * 16;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) rf[s][i] = *reinterpret_cast<const u32x4 *>(sa + a_row + i * MF * RB + at);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) cf[s][j] = *reinterpret_cast<const u32x4 *>(sb + b_row + j * MF * RB + at);
+        }
+        __builtin_amdgcn_sched_barrier(0); // keep the reads ahead of the products
+#pragma unroll
+        for (int s = 0; s < GROUP; ++s)
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) M::run(acc[i][j], rf[s][i], cf[s][j]);
+    };
+
     // prologue: fill all but one buffer
     int requested = 0;
     for (; requested < nst - 1 && requested < kt_count; ++requested) request(requested, requested);
@@ -970,7 +1029,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
             const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
             if constexpr (decltype(unroll_steps)::value) {
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
+                for (int ks = 0; ks < NKS; ks += GROUP) k_group(sa, sb, ks);
             } else {
 #pragma unroll 1
                 for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
