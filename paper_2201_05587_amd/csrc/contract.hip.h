@@ -43,14 +43,16 @@ template <> struct ElemOf<TT_BF16> {
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-// float -> bf16, round to nearest, ties to even; NaN stays a quiet NaN.
-__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+// two floats -> two bf16 in one register (first in the low half), round to nearest, ties to even; NaN stays
+// a quiet NaN.  gfx950 converts a pair in one instruction.
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ uint32_t pack_bf16x2(float first, float second)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const f32x2 v = {first, second};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) { return (uint16_t)pack_bf16x2(f, 0.0f); }
 
 template <int DT> __device__ __forceinline__ float load_as_float(const void *p, int64_t i)
 {
@@ -75,6 +77,26 @@ __device__ __forceinline__ float apply_act(float v, int act)
     case ACT_RELU6: return fminf(fmaxf(v, 0.0f), 6.0f);
     case ACT_GELU: return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
     default: return v;
+    }
+}
+
+// The same on N values with one (uniform) branch for all of them.
+template <int N> __device__ __forceinline__ void apply_act_all(float (&v)[N], int act)
+{
+    switch (act) {
+    case ACT_RELU:
+#pragma unroll
+        for (int e = 0; e < N; ++e) v[e] = fmaxf(v[e], 0.0f);
+        break;
+    case ACT_RELU6:
+#pragma unroll
+        for (int e = 0; e < N; ++e) v[e] = fminf(fmaxf(v[e], 0.0f), 6.0f);
+        break;
+    case ACT_GELU:
+#pragma unroll
+        for (int e = 0; e < N; ++e) v[e] = 0.5f * v[e] * (1.0f + erff(v[e] * 0.70710678118654752f));
+        break;
+    default: break;
     }
 }
 
@@ -531,19 +553,27 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                     continue;
                 }
                 if (vc == 8 && DT == TT_BF16) {
-                    u32x4 resv = {0u, 0u, 0u, 0u}, biasv = {0u, 0u, 0u, 0u};
-                    if (g.has_res)
-                        resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
-                    if (g.has_bias) biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
+                    // bias first, then the residual (the order of the element-wise path)
+                    if (g.has_bias) {
+                        const u32x4 biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            val[2 * h] += __uint_as_float(biasv[h] << 16);
+                            val[2 * h + 1] += __uint_as_float(biasv[h] & 0xffff0000u);
+                        }
+                    }
+                    if (g.has_res) {
+                        const u32x4 resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            val[2 * h] += __uint_as_float(resv[h] << 16);
+                            val[2 * h + 1] += __uint_as_float(resv[h] & 0xffff0000u);
+                        }
+                    }
+                    apply_act_all(val, g.act);
                     u32x4 outv;
 #pragma unroll
-                    for (int h = 0; h < 4; ++h) {
-                        float a = val[2 * h] + __uint_as_float(biasv[h] << 16) + __uint_as_float(resv[h] << 16);
-                        float b = val[2 * h + 1] + __uint_as_float(biasv[h] & 0xffff0000u) +
-                                  __uint_as_float(resv[h] & 0xffff0000u);
-                        outv[h] = (uint32_t)float_to_bf16_bits(apply_act(a, g.act)) |
-                                  ((uint32_t)float_to_bf16_bits(apply_act(b, g.act)) << 16);
-                    }
+                    for (int h = 0; h < 4; ++h) outv[h] = pack_bf16x2(val[2 * h], val[2 * h + 1]);
                     *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
                 } else if (vc >= 4 && DT == TT_F32) {
 #pragma unroll
@@ -555,9 +585,9 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                         if (g.has_bias)
                             add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
                         if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) r[e] = apply_act(r[e] + add[e], g.act);
-                        *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = r;
+                        float sum[4] = {r[0] + add[0], r[1] + add[1], r[2] + add[2], r[3] + add[3]};
+                        apply_act_all(sum, g.act);
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = f32x4{sum[0], sum[1], sum[2], sum[3]};
                     }
                 } else {
                     for (int e = 0; e < vc; ++e) {
