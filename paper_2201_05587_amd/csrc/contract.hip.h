@@ -496,6 +496,29 @@ template <int TM, int WM, int WN, int MF> struct TileOut {
     }
 };
 
+// `count` (1..8) consecutive outputs of one row, starting at element `at` of the output (column `n`), from
+// the 8 staged sums lo, hi: bias, residual, activation, conversion and store one element at a time, or the
+// raw sums into the split-K workspace.  Everything is passed by value so that the call needs no stack.
+template <int DT>
+__device__ __noinline__ void write_row_elements(float *ws, void *out, const void *bias, const void *res, bool partial,
+                                                bool has_bias, bool has_res, int act, int64_t at, int n, int count,
+                                                f32x4 lo, f32x4 hi)
+{
+#pragma unroll 1
+    for (int e = 0; e < count; ++e) {
+        float a = lo[0];
+#pragma unroll
+        for (int t = 1; t < 8; ++t) a = e == t ? (t < 4 ? lo[t] : hi[t - 4]) : a; // (registers cannot be indexed)
+        if (partial) {
+            ws[at + e] = a;
+            continue;
+        }
+        if (has_bias) a += load_as_float<DT>(bias, n + e);
+        if (has_res) a += load_as_float<DT>(res, at + e);
+        store_from_float<DT>(out, at + e, apply_act(a, act));
+    }
+}
+
 template <int DT, int TM, int WM, int WN, int MF, typename Acc>
 __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
                                            unsigned char *smem, int wave, int lane)
@@ -509,6 +532,8 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
     const int64_t mn = (int64_t)g.M * g.N;
     float *ws = g.ws + ((int64_t)tc.lo * g.batch) * mn;
     const int vc = g.eff_vec_c; // consecutive outputs of a row that are all inside or all outside the matrix
+    const bool whole = DT == TT_BF16 ? vc == 8 : vc >= 4; // rows are whole 16-byte vectors long
+    const int64_t out_base = (int64_t)bidx * mn;
     const int cg = lane % CG;
     const int first = tc.n0 + T::col(wave, lane);
 
@@ -535,27 +560,18 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
             const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row_l * ESTRIDE + cg * 8 + 4);
             float val[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             const int m = tc.m0 + T::row(wave, lane, i, ps);
-            if (m >= g.M) continue;
-            // groups of vc consecutive columns
-            for (int e0 = 0; e0 < 8; e0 += vc) {
-                const int n = first + e0;
-                if (n >= g.N) break;
-                const int64_t idx = (int64_t)bidx * mn + (int64_t)m * g.N + n;
+            if (m >= g.M || first >= g.N) continue;
+            const int64_t row_at = out_base + (int64_t)m * g.N + first;
+            if (whole) {
+                // Rows are whole vectors long: the lane's 8 columns (fp32: its two groups of 4) need no
+                // further checks and no loop.  Bias first, then the residual (the order of the
+                // element-wise path).
                 if (partial) {
-                    if (vc == 8) {
-                        *reinterpret_cast<f32x4 *>(ws + idx) = lo;
-                        *reinterpret_cast<f32x4 *>(ws + idx + 4) = hi;
-                    } else if (vc == 4) {
-                        *reinterpret_cast<f32x4 *>(ws + idx) = e0 == 0 ? lo : hi;
-                    } else {
-                        for (int e = 0; e < vc; ++e) ws[idx + e] = val[e0 + e];
-                    }
-                    continue;
-                }
-                if (vc == 8 && DT == TT_BF16) {
-                    // bias first, then the residual (the order of the element-wise path)
+                    *reinterpret_cast<f32x4 *>(ws + row_at) = lo;
+                    if (DT == TT_BF16 || first + 4 < g.N) *reinterpret_cast<f32x4 *>(ws + row_at + 4) = hi;
+                } else if constexpr (DT == TT_BF16) {
                     if (g.has_bias) {
-                        const u32x4 biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + n);
+                        const u32x4 biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + first);
 #pragma unroll
                         for (int h = 0; h < 4; ++h) {
                             val[2 * h] += __uint_as_float(biasv[h] << 16);
@@ -563,7 +579,7 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                         }
                     }
                     if (g.has_res) {
-                        const u32x4 resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + idx);
+                        const u32x4 resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + row_at);
 #pragma unroll
                         for (int h = 0; h < 4; ++h) {
                             val[2 * h] += __uint_as_float(resv[h] << 16);
@@ -574,30 +590,27 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                     u32x4 outv;
 #pragma unroll
                     for (int h = 0; h < 4; ++h) outv[h] = pack_bf16x2(val[2 * h], val[2 * h + 1]);
-                    *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + idx) = outv;
-                } else if (vc >= 4 && DT == TT_F32) {
+                    *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + row_at) = outv;
+                } else {
 #pragma unroll
                     for (int q4 = 0; q4 < 2; ++q4) {
-                        if (q4 * 4 < e0 || q4 * 4 >= e0 + vc) continue;
-                        f32x4 r = q4 == 0 ? lo : hi;
-                        const int64_t at = idx + (q4 * 4 - e0);
+                        if (q4 == 1 && first + 4 >= g.N) break;
+                        const int64_t at = row_at + 4 * q4;
                         f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
-                        if (g.has_bias)
-                            add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + n + (q4 * 4 - e0));
+                        if (g.has_bias) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + first + 4 * q4);
                         if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
-                        float sum[4] = {r[0] + add[0], r[1] + add[1], r[2] + add[2], r[3] + add[3]};
+                        float sum[4] = {val[4 * q4] + add[0], val[4 * q4 + 1] + add[1], val[4 * q4 + 2] + add[2],
+                                        val[4 * q4 + 3] + add[3]};
                         apply_act_all(sum, g.act);
                         *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = f32x4{sum[0], sum[1], sum[2], sum[3]};
                     }
-                } else {
-                    for (int e = 0; e < vc; ++e) {
-                        float a = val[e0 + e];
-                        if (g.has_bias) a += load_as_float<DT>(g.bias, n + e);
-                        if (g.has_res) a += load_as_float<DT>(g.res, idx + e);
-                        store_from_float<DT>(g.out, idx + e, apply_act(a, g.act));
-                    }
                 }
+                continue;
             }
+            // any other row length: element by element, out of line (rare, and it must not cost the
+            // path above registers)
+            write_row_elements<DT>(ws, g.out, g.bias, g.res, partial, g.has_bias, g.has_res, g.act, row_at, first,
+                                   min(8, g.N - first), lo, hi);
         }
     }
 }
