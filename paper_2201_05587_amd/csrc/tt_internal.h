@@ -20,12 +20,32 @@ constexpr int kLdsBudget = 160 * 1024;
 
 enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
 
+// Exact n / d for 0 <= n < 2^31 and 1 <= d < 2^31 by one widening multiply:
+// magic = ceil(2^(31+shift) / d) with shift = ceil(log2 d) fits 32 bits, and the
+// error n * (magic * d - 2^(31+shift)) / (d * 2^(31+shift)) stays below 1/d.
+struct FastDiv {
+    uint32_t magic, shift;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.shift = 0;
+    while ((1ull << f.shift) < d) ++f.shift;
+    const uint64_t pw = 1ull << (31 + f.shift);
+    f.magic = (uint32_t)((pw + d - 1) / d);
+    return f;
+}
+TT_HD uint32_t fast_div(uint32_t n, const FastDiv &f) { return (uint32_t)((((uint64_t)n * f.magic) >> 31) >> f.shift); }
+
 // What a workgroup needs to find its tile: the integer fields of the plan the index map reads.
 struct TileMap {
     int32_t sketch, order, grid;
     int32_t tiles_m, tiles_n, tile_m, tile_n, tile_k;
     int32_t M, N, K;
     int32_t eff_split_k, k_iters, k_tiles;
+    // reciprocals of the map's divisors (a workgroup's first instructions; integer division is emulated
+    // on the GPU): tiles_m * tiles_n, tiles_m, tiles_n, kGroupM * tiles_n, eff_split_k
+    FastDiv div_tiles, div_m, div_n, div_band, div_split;
 };
 
 struct TileCoord {
@@ -44,22 +64,27 @@ TT_HD TileCoord decode_tile(const TileMap &p, int32_t wg)
         L = x * per + (x < rem ? x : rem) + j;
     }
     const int32_t T = p.tiles_m * p.tiles_n;
-    const int32_t slab = L / T, t = L % T;
+    const int32_t slab = (int32_t)fast_div((uint32_t)L, p.div_tiles), t = L - slab * T;
     const int32_t base = p.order % 3;
     int32_t im, in;
     if (base == 0) {
-        im = t % p.tiles_m;
-        in = t / p.tiles_m;
+        in = (int32_t)fast_div((uint32_t)t, p.div_m);
+        im = t - in * p.tiles_m;
     } else if (base == 1) {
-        in = t % p.tiles_n;
-        im = t / p.tiles_n;
+        im = (int32_t)fast_div((uint32_t)t, p.div_n);
+        in = t - im * p.tiles_n;
     } else {
         const int32_t width = kGroupM * p.tiles_n;
-        const int32_t first = (t / width) * kGroupM;
+        const int32_t band = (int32_t)fast_div((uint32_t)t, p.div_band);
+        const int32_t first = band * kGroupM, at = t - band * width;
         const int32_t left = p.tiles_m - first;
-        const int32_t gsize = left < kGroupM ? left : kGroupM;
-        im = first + (t % width) % gsize;
-        in = (t % width) / gsize;
+        if (left >= kGroupM) {
+            in = at / kGroupM;
+            im = first + at % kGroupM;
+        } else { // the last, lower band
+            in = at / left;
+            im = first + at % left;
+        }
     }
     TileCoord c;
     c.m0 = im * p.tile_m;
@@ -77,8 +102,8 @@ TT_HD TileCoord decode_tile(const TileMap &p, int32_t wg)
         c.k0 = 0;
         c.k_ext = p.K;
     } else {
-        c.hi = slab / p.eff_split_k;
-        c.lo = slab % p.eff_split_k;
+        c.hi = (int32_t)fast_div((uint32_t)slab, p.div_split);
+        c.lo = slab - c.hi * p.eff_split_k;
         const int32_t kt0 = c.lo * p.k_iters;
         int32_t kt1 = kt0 + p.k_iters;
         if (kt1 > p.k_tiles) kt1 = p.k_tiles;
@@ -106,25 +131,14 @@ inline TileMap tile_map_of(const tt_plan &pl)
     m.eff_split_k = pl.eff_split_k;
     m.k_iters = pl.k_iters;
     m.k_tiles = pl.k_tiles;
+    const auto at_least_one = [](int32_t v) { return (uint32_t)(v > 0 ? v : 1); };
+    m.div_tiles = make_fastdiv(at_least_one(pl.tiles_m * pl.tiles_n));
+    m.div_m = make_fastdiv(at_least_one(pl.tiles_m));
+    m.div_n = make_fastdiv(at_least_one(pl.tiles_n));
+    m.div_band = make_fastdiv(at_least_one(kGroupM * pl.tiles_n));
+    m.div_split = make_fastdiv(at_least_one(pl.eff_split_k));
     return m;
 }
-
-// Exact n / d for 0 <= n < 2^31 and 1 <= d < 2^31 by one widening multiply:
-// magic = ceil(2^(31+shift) / d) with shift = ceil(log2 d) fits 32 bits, and the
-// error n * (magic * d - 2^(31+shift)) / (d * 2^(31+shift)) stays below 1/d.
-struct FastDiv {
-    uint32_t magic, shift;
-};
-inline FastDiv make_fastdiv(uint32_t d)
-{
-    FastDiv f;
-    f.shift = 0;
-    while ((1ull << f.shift) < d) ++f.shift;
-    const uint64_t pw = 1ull << (31 + f.shift);
-    f.magic = (uint32_t)((pw + d - 1) / d);
-    return f;
-}
-TT_HD uint32_t fast_div(uint32_t n, const FastDiv &f) { return (uint32_t)((((uint64_t)n * f.magic) >> 31) >> f.shift); }
 
 // Operand families of the matrix-core contraction kernel.
 enum Family {
