@@ -285,6 +285,8 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
         int32_t r, j, dr, dj, runp, row_stride, numel;
         u32x4 raw[NL];
         int32_t span[NL]; // without VEC: first real element of the item in flight | (one past the last) << 8
+                          // | bf16: (the item starts in the upper half of its first 32-bit word) << 16
+        uint32_t tail[NL]; // bf16 without VEC: the 32-bit word after raw (the item's last element if it starts odd)
     };
 
     static __device__ __forceinline__ void init(State &st, const ContractArgs &g, int row0, int k0, int tid)
@@ -346,8 +348,19 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
                 const bool any = row_ok & (hi > lo);
                 const int start = st.origin[i] + kterm;
                 st.span[i] = any ? (lo | (hi << 8)) : 0;
-                if (!any || (start >= 0 && start + CH <= st.numel)) {
-                    st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, any ? at : kOutOfRange, 0, 0);
+                if constexpr (DT == TT_BF16) st.tail[i] = 0u;
+                if (!any || (start >= 0 && start + CH + 2 <= st.numel)) {
+                    if constexpr (DT == TT_BF16) {
+                        // Items start at any even byte.  Fetch the five 32-bit words that cover the item from
+                        // its word-aligned start (a 16-byte load that is not word-aligned is split into
+                        // many requests) and shift them into place when the slice is written to LDS.
+                        const uint32_t at4 = at & ~3u;
+                        st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, any ? at4 : kOutOfRange, 0, 0);
+                        st.tail[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, any ? at4 + 16u : kOutOfRange, 0, 0);
+                        st.span[i] |= (int32_t)(at & 2u) << 15;
+                    } else {
+                        st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, any ? at : kOutOfRange, 0, 0);
+                    }
                 } else {
                     // the first or the last item of the whole tensor: element by element
 #pragma unroll
@@ -382,7 +395,15 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
             const int row = first + i * STEP;
             if (TOTAL % THREADS != 0 && row >= ROWS) continue;
             u32x4 v = st.raw[i];
-            if constexpr (!VEC) v = keep_range<DT>(v, st.span[i] & 0xff, st.span[i] >> 8);
+            if constexpr (!VEC) {
+                if constexpr (DT == TT_BF16) {
+                    if (st.span[i] & (1 << 16)) {
+                        v = u32x4{__builtin_amdgcn_alignbyte(v[1], v[0], 2), __builtin_amdgcn_alignbyte(v[2], v[1], 2),
+                                  __builtin_amdgcn_alignbyte(v[3], v[2], 2), __builtin_amdgcn_alignbyte(st.tail[i], v[3], 2)};
+                    }
+                }
+                v = keep_range<DT>(v, st.span[i] & 0xff, (st.span[i] >> 8) & 0xff);
+            }
             *reinterpret_cast<u32x4 *>(lds + row * ROWB + chunk * 16) = v;
         }
     }
