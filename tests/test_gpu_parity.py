@@ -185,6 +185,20 @@ def test_dense_odd_k_uses_narrow_loads(api, P):
         P.check_kernel(k, [None, mfma(api, k.cls, 32, 32, tk, 16, 16, 16, vec=8), mfma(api, k.cls, 32, 32, tk, 16, 16, 16, vec=2)])
 
 
+def test_output_rows_of_every_vector_width(api, P):
+    """N a multiple of 8, of 4, of 2 and odd: whole-vector epilogue, and the element loop, with bias,
+    residual, every activation class and split reductions (raw sums to the workspace)."""
+    for dt in (wl.F32, wl.BF16):
+        tk = 16 if dt == wl.F32 else 32
+        for n in (96, 92, 90, 91):
+            for cls in (wl.CLS_DENSE_ADD, wl.CLS_DENSE_BIAS_GELU):
+                k = wl.Kernel(cls, wl.GemmShape(1, 70, n, 8 * tk, 1, dt), 1, f"dense_n{n}_{cls}_{dt}")
+                P.check_kernel(k, [mfma(api, cls, 32, 32, tk, 16, 16, 16), mfma(api, cls, 64, 64, tk, 32, 32, 32, split_k=2),
+                                   mfma(api, cls, 64, 64, tk * 2, 32, 32, 16, stages=3)], seed=n)
+            c = conv_kernel(wl.CLS_CONV2D_BIAS_ADD_RELU, 2, 16, 9, n, 3, 1, dtype=dt)
+            P.check_kernel(c, [mfma(api, c.cls, 64, 32, tk, 32, 32, 16), mfma(api, c.cls, 32, 64, tk, 16, 32, 16, split_k=3)], seed=n)
+
+
 def test_gemv_sketch_resnet_classifier(api, P):
     k = wl.resnet18_kernels()[-1]
     assert k.gemm_extents() == (1, 1, 1000, 512)
