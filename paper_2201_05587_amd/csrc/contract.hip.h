@@ -1048,24 +1048,28 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
             for (int j = 0; j < NJ; ++j) M::run(acc[i][j], rf[i], cf[j]);
     };
 
-    // GROUP consecutive steps with all their fragment reads issued before the first product
-    auto k_group = [&](const unsigned char *sa, const unsigned char *sb, int ks0) {
+    // GROUP consecutive steps: all their fragment reads are issued before the first product
+    struct Fragments {
         u32x4 rf[GROUP][NI], cf[GROUP][NJ];
+    };
+    auto read_group = [&](Fragments &f, const unsigned char *sa, const unsigned char *sb, int ks0) {
 #pragma unroll
         for (int s = 0; s < GROUP; ++s) {
             const int at = (((ks0 + s) * LG + lane_g) ^ swz) * 16;
 #pragma unroll
-            for (int i = 0; i < NI; ++i) rf[s][i] = *reinterpret_cast<const u32x4 *>(sa + a_row + i * MF * RB + at);
+            for (int i = 0; i < NI; ++i) f.rf[s][i] = *reinterpret_cast<const u32x4 *>(sa + a_row + i * MF * RB + at);
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) cf[s][j] = *reinterpret_cast<const u32x4 *>(sb + b_row + j * MF * RB + at);
+            for (int j = 0; j < NJ; ++j) f.cf[s][j] = *reinterpret_cast<const u32x4 *>(sb + b_row + j * MF * RB + at);
         }
-        __builtin_amdgcn_sched_barrier(0); // keep the reads ahead of the products
+        __builtin_amdgcn_sched_barrier(0); // keep the reads ahead of what follows
+    };
+    auto multiply_group = [&](const Fragments &f) {
 #pragma unroll
         for (int s = 0; s < GROUP; ++s)
 #pragma unroll
             for (int i = 0; i < NI; ++i)
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) M::run(acc[i][j], rf[s][i], cf[s][j]);
+                for (int j = 0; j < NJ; ++j) M::run(acc[i][j], f.rf[s][i], f.cf[s][j]);
     };
 
     // prologue: fill all but one buffer
@@ -1085,16 +1089,29 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
             else
                 wait_loads_outstanding<0>();
             __syncthreads(); // slice `it` is visible to all waves, and all waves are done with slice it - 1
-            if (requested < kt_count) {
-                request(requested, fill);
-                ++requested;
-                fill = fill + 1 == nst ? 0 : fill + 1;
-            }
             const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
+            auto request_next = [&]() {
+                if (requested < kt_count) {
+                    request(requested, fill); // into the buffer that held slice it - 1
+                    ++requested;
+                    fill = fill + 1 == nst ? 0 : fill + 1;
+                }
+            };
             if constexpr (decltype(unroll_steps)::value) {
+                // The first fragment reads go out before the next slice is requested: the address
+                // arithmetic of the requests then runs while the LDS answers, instead of after it (a wave
+                // executes in order, and a workgroup that owns its CU has few waves to fill the gap).
+                Fragments f;
+                read_group(f, sa, sb, 0);
+                request_next();
+                multiply_group(f);
 #pragma unroll
-                for (int ks = 0; ks < NKS; ks += GROUP) k_group(sa, sb, ks);
+                for (int ks = GROUP; ks < NKS; ks += GROUP) {
+                    read_group(f, sa, sb, ks);
+                    multiply_group(f);
+                }
             } else {
+                request_next();
 #pragma unroll 1
                 for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
             }
