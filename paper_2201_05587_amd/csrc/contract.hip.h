@@ -1079,20 +1079,22 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     // compiler shuttle the accumulators between the register sets of the two paths on every slice).
     auto k_loop = [&](auto unroll_steps) {
         int cur = 0, fill = requested == nst - 1 ? nst - 1 : 0; // buffer to compute on / buffer the next request fills
-        for (int it = 0; it < kt_count; ++it) {
-            // slice `it` has arrived once at most (requested - it - 1) younger slices are outstanding
-            const int younger = requested - it - 1;
+        // One slice: wait until at most `younger` later slices are outstanding, publish it, compute on it;
+        // `requesting` iterations also ask for slice it + stages - 1.
+        auto wait_for_slice = [&](int younger) {
             if (younger >= 2)
                 wait_loads_outstanding<2 * LPS>();
             else if (younger == 1)
                 wait_loads_outstanding<LPS>();
             else
                 wait_loads_outstanding<0>();
-            __syncthreads(); // slice `it` is visible to all waves, and all waves are done with slice it - 1
+        };
+        auto slice = [&](auto requesting) {
+            __syncthreads(); // the slice is visible to all waves, and all waves are done with the one before it
             const unsigned char *sa = smem + cur * STAGE_BYTES, *sb = sa + A_BYTES;
             auto request_next = [&]() {
-                if (requested < kt_count) {
-                    request(requested, fill); // into the buffer that held slice it - 1
+                if constexpr (decltype(requesting)::value) {
+                    request(requested, fill); // into the buffer that held the slice before this one
                     ++requested;
                     fill = fill + 1 == nst ? 0 : fill + 1;
                 }
@@ -1116,6 +1118,21 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
                 for (int ks = 0; ks < NKS; ++ks) k_step(sa, sb, ks);
             }
             cur = cur + 1 == nst ? 0 : cur + 1;
+        };
+        // Steady state: while slices remain to be requested, stages - 2 younger slices are in flight at the
+        // top of every iteration (the prologue requested stages - 1 of them), so the wait is the same each time.
+        int it = 0;
+        for (; requested < kt_count; ++it) {
+            if (nst == 4)
+                wait_loads_outstanding<2 * LPS>();
+            else
+                wait_loads_outstanding<LPS>();
+            slice(std::true_type{});
+        }
+        // Drain: everything is requested; slice `it` has arrived once at most kt_count - it - 1 younger ones are outstanding.
+        for (; it < kt_count; ++it) {
+            wait_for_slice(kt_count - it - 1);
+            slice(std::false_type{});
         }
     };
     if (NKS == 1 || g.unroll >= 2)
