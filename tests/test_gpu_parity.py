@@ -166,6 +166,24 @@ def test_async_ring_dense_and_batch_matmul(api, P):
         P.check_kernel(odd, [rec])
 
 
+def test_async_ring_with_fewer_slices_than_stages_and_at_the_loop_boundaries(api, P):
+    """1..6 slices under 3 and 4 stages: prologue only, drain only, and one or more steady-state iterations."""
+    for dt in (wl.F32, wl.BF16):
+        tk = 16 if dt == wl.F32 else 32
+        for slices in (1, 2, 3, 4, 5, 6):
+            k = wl.Kernel(wl.CLS_DENSE_BIAS_RELU, wl.GemmShape(1, 96, 80, tk * slices, 1, dt), 1, f"dense_{slices}slices_{dt}")
+            scheds = [mfma(api, k.cls, 64, 64, tk, 32, 32, 16, stages=3), mfma(api, k.cls, 64, 64, tk, 32, 32, 16, stages=4)]
+            if slices >= 3:
+                scheds.append(mfma(api, k.cls, 64, 64, tk, 32, 32, 16, stages=4, split_k=2))   # uneven halves
+            for s_ in scheds:
+                assert api.variant_name(api.tt_schedule_apply(s_, k.cls, k.shape)).startswith("tt::contract_async_kernel")
+            P.check_kernel(k, scheds, seed=slices)
+            c = conv_kernel(wl.CLS_CONV2D_BIAS_RELU, 1, tk * slices, 6, 32, 1, 2, dtype=dt)   # strided 1x1: gathered, K = C
+            if c.shape.c % (8 if dt == wl.BF16 else 4) == 0:
+                P.check_kernel(c, [mfma(api, c.cls, 32, 32, tk, 16, 16, 16, stages=4), mfma(api, c.cls, 64, 32, tk, 32, 16, 16, stages=3)],
+                               seed=slices + 10)
+
+
 # ---- dense / batch matmul -------------------------------------------------------------------------
 def test_dense_classes(api, P):
     for cls in (wl.CLS_DENSE_ADD, wl.CLS_DENSE_BIAS_RELU, wl.CLS_DENSE_BIAS_GELU):
