@@ -181,8 +181,8 @@ def cpu_baseline_leg(wl, targets, budget_s=25.0):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(kernel/schedule pairs are independent and would shard by target kernel, see DESIGN.md)")
+        print("bench.py: this library runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(kernel/schedule pairs are independent and would shard by target kernel)")
         sys.exit(2)
     import torch
     from paper_2201_05587_amd import api, harness, traffic, tune

@@ -20,6 +20,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "tt_internal.h"
@@ -1142,6 +1143,24 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane);
 }
 
+// More than 48 KB of dynamic LDS has to be enabled per kernel.  Remembers the largest size enabled so far
+// (one device per process); host threads may launch the same kernel concurrently.
+struct DynamicLdsLimit {
+    std::mutex guard;
+    int raised = 0;
+    int raise_to(const void *kernel, int lds_bytes)
+    {
+        if (lds_bytes <= 48 * 1024) return TT_OK;
+        std::lock_guard<std::mutex> lock(guard);
+        if (lds_bytes > raised) {
+            const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e != hipSuccess) return note_hip_error((int)e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+            raised = lds_bytes;
+        }
+        return TT_OK;
+    }
+};
+
 template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int AM>
 int launch_contract(const ContractArgs &args, int grid, int lds_bytes, void *stream)
 {
@@ -1149,13 +1168,8 @@ int launch_contract(const ContractArgs &args, int grid, int lds_bytes, void *str
     // the epilogue stages one band of MF rows per wave in the same LDS
     constexpr int EPI_BYTES = (TM / WM) * (TN / WN) * MF * (WN + (MF == 32 ? 8 : 4)) * 4;
     if (lds_bytes < EPI_BYTES) lds_bytes = EPI_BYTES;
-    static int raised = 0; // largest dynamic-LDS size this kernel has been enabled for
-    if (lds_bytes > 48 * 1024 && lds_bytes > raised) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return note_hip_error((int)e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
-        raised = lds_bytes;
-    }
+    static DynamicLdsLimit limit; // per kernel instance
+    if (const int rc = limit.raise_to(reinterpret_cast<const void *>(kern), lds_bytes); rc != TT_OK) return rc;
     constexpr int THREADS = (TM / WM) * (TN / WN) * 64;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds_bytes, static_cast<hipStream_t>(stream), args);
     const hipError_t e = hipGetLastError();
@@ -1168,13 +1182,8 @@ int launch_contract_async(const ContractArgs &args, int grid, int lds_bytes, voi
     auto kern = contract_async_kernel<DT, FAM, TM, TN, TK, WM, WN, MF>;
     constexpr int EPI_BYTES = (TM / WM) * (TN / WN) * MF * (WN + (MF == 32 ? 8 : 4)) * 4;
     if (lds_bytes < EPI_BYTES) lds_bytes = EPI_BYTES;
-    static int raised = 0;
-    if (lds_bytes > 48 * 1024 && lds_bytes > raised) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return note_hip_error((int)e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
-        raised = lds_bytes;
-    }
+    static DynamicLdsLimit limit; // per kernel instance
+    if (const int rc = limit.raise_to(reinterpret_cast<const void *>(kern), lds_bytes); rc != TT_OK) return rc;
     constexpr int THREADS = (TM / WM) * (TN / WN) * 64;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds_bytes, static_cast<hipStream_t>(stream), args);
     const hipError_t e = hipGetLastError();
