@@ -121,8 +121,7 @@ typedef struct tt_gemm_shape {
  * depends on the size of the kernel it was tuned for, so it can be re-applied
  * to any kernel of its class (Section 4.1's Split(N, N/8, 8) form).
  *
- * Meaning per sketch (GEMM view: conv M = n*Ho*Wo, N = k, K = r * (s*c rounded up to whole
- * 16-byte items), which is c*r*s whenever s*c fills whole items; dense and
+ * Meaning per sketch (GEMM view: conv M = n*Ho*Wo, N = k, K = c*r*s; dense and
  * batch matmul M, N, K per batch; depthwise M = Ho, N = Wo, "K" = n*c planes):
  *   TT_SK_MFMA   tile_m x tile_n x tile_k workgroup tile (Split level 1, powers of two 16..256,
  *                tile_k in 16/32/64/128); wave_m x wave_n wave tile (Split level 2); mfma = edge
@@ -138,7 +137,8 @@ typedef struct tt_gemm_shape {
  *   TT_SK_DWCONV tile_m x tile_n output rows x cols and tile_k lanes along the plane axis per workgroup,
  *                wave_m x wave_n outputs per thread; vec = channel-contiguous planes per lane (reformulated
  *                to what divides the channel count; the workgroup then covers tile_k * vec planes);
- *                stages = 2 stages the input patch through LDS (one plane per lane), mfma = 0.
+ *                stages = 2 stages the input patch through LDS (kernel with one plane per lane only: a
+ *                plan with more has variant_id = -1), mfma = 0.
  *   TT_SK_DIRECT all tile and wave fields 1, mfma = 0.
  */
 typedef struct tt_schedule {
@@ -159,9 +159,18 @@ typedef struct tt_schedule {
 } tt_schedule;
 
 /*
- * The integer plan tt_schedule_apply derives.  All fields up to workspace_bytes
- * are a pure function of (record, class, shape, flags) and are specified
- * independently of the kernels; variant_id is the library's own lookup.
+ * The integer plan tt_schedule_apply derives, a pure function of (record, class, shape, flags).
+ * Two kinds of fields:
+ *   method   what Sections 4.1 / 4.2 define, independent of how a kernel is written: status and
+ *            reason (class mismatch, a factor larger than its loop, strict divisibility, split of
+ *            the reduction, grid), the GEMM view M, N, K, the kept inner factors, the derived outer
+ *            extents and tails, eff_split_k, k_iters, slabs, order, grid, block, workspace_bytes;
+ *   library  how this library's kernels fetch and stage the tiles: eff_vec_*, eff_unroll, stages
+ *            (after reformulation), lds_bytes, variant_id, and the reasons TT_R_LDS and
+ *            TT_R_K_GRANULE, which are checked after every method rule.  lds_bytes is stages times
+ *            the per-stage size the compiled kernel variant reports (tt_variant_info); it is 0 when
+ *            no variant implements the plan (variant_id = -1: the operator entry points then return
+ *            TT_ERR_UNSUPPORTED).
  */
 typedef struct tt_plan {
     int32_t status, reason;
@@ -177,7 +186,8 @@ typedef struct tt_plan {
     int32_t grid, block;                 /* workgroups, threads per workgroup             */
     int32_t lds_bytes;
     int64_t workspace_bytes;
-    int32_t variant_id;                  /* compiled kernel variant, -1 if none           */
+    int32_t variant_id;                  /* compiled kernel variant (matrix-core sketch) or 0;
+                                            -1 if no kernel implements the plan             */
     int32_t reserved;
 } tt_plan;
 
@@ -325,13 +335,17 @@ int tt_run_kernels(const tt_kernel_desc *kernels, const tt_schedule *const *sche
 int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out, int cap);
 
 /*
- * Template arguments of a compiled matrix-core kernel variant (tt_plan.variant_id): out[10] =
+ * Template arguments of a compiled matrix-core kernel variant (tt_plan.variant_id), and what the
+ * kernel itself reports about its use of the chip: out[12] =
  * {dtype, family (0 conv, 1 GEMM with [N][K] B, 2 GEMM with [K][N] B), tile_m, tile_n, tile_k, wave_m,
  * wave_n, mfma, bytes per gathered load (conv family; 0 otherwise), pipeline (0 register-staged,
  * symbol contract_kernel with the first nine arguments; 1 asynchronous ring, symbol
- * contract_async_kernel with the first eight)}.  TT_ERR_BAD_ARG for an id outside the table.
+ * contract_async_kernel with the first eight), LDS bytes of one pipeline stage, reduction elements one
+ * matrix-core step consumes (tile_k is a multiple of it)}.  TT_ERR_BAD_ARG for an id outside the table.
  */
-int tt_variant_info(int variant_id, int32_t out[10]);
+int tt_variant_info(int variant_id, int32_t out[12]);
+/* Number of compiled variants: ids 0 .. tt_num_variants() - 1. */
+int tt_num_variants(void);
 
 /*
  * Which pre-tuned model to take the donor schedules from (Section 4.4.2, Eq. 1): for every candidate

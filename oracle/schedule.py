@@ -13,12 +13,16 @@ What the paper fixes (Sections 4.1-4.3) and what is written out here:
   divides.  Section 4.2 adds the failure case: a factor larger than the loop
   gives invalid code.
 * ``apply``: the same rule applied to a GPU schedule record.  Inner factors
-  (workgroup tile, wave tile, MFMA edge, vector width, unroll depth, parallel
-  split of the reduction) are kept, every outer extent is derived from the
-  TARGET kernel's shape; a record of another kernel class is always invalid
-  (Section 4.2); vector width and unroll depth are reformulated rather than
-  rejected (Section 4.1: "unroll to its maximum depth" is valid for any trip
-  count).  The result is an integer *plan*.
+  (workgroup tile, wave tile, MFMA edge, parallel split of the reduction) are
+  kept, every outer extent is derived from the TARGET kernel's shape; a record
+  of another kernel class is always invalid (Section 4.2).  The result is an
+  integer *plan* holding what the method defines: validity and its reason,
+  the GEMM view of the kernel (convolution: M = n * Ho * Wo, N = k,
+  K = c * r * s), tiles, tails, the split of the reduction, grid and
+  workspace.  How a kernel implementation stages its tiles (on-chip memory
+  bytes, pipeline depth, access widths of the matrix-core sketch) is NOT
+  modelled here: those fields belong to the library and are checked against
+  what its kernels export.
 * ``plan_tile``: workgroup id -> (batch, k-split, tile origin and clipped
   extents), a closed-form integer map; the device code must agree bit for bit.
 * ``select`` / ``evaluation_count``: Section 4.3's sweep once the times are
@@ -69,14 +73,12 @@ R_FACTOR_GT_N = 2
 R_FACTOR_GT_K = 3
 R_NOT_DIVISIBLE = 4
 R_SPLIT_K = 5
-R_LDS = 6
-R_K_GRANULE = 7
+# 6 and 7 are the library's own resource reasons (on-chip memory, matrix-core K step): never produced here
 R_GRID = 8
 R_SKETCH_CLASS = 9
 
 STRICT_DIVISIBLE = 1  # flag bit: Section 4.1's divisibility reading ({N : f | N})
 
-LDS_BUDGET = 160 * 1024
 XCDS = 8
 GROUP_M = 8
 
@@ -84,8 +86,7 @@ RECORD_FIELDS = ("cls", "sketch", "tile_m", "tile_n", "tile_k", "wave_m", "wave_
                  "order", "vec", "unroll", "stages")
 PLAN_FIELDS = ("status", "reason", "sketch", "batch", "M", "N", "K", "tile_m", "tile_n", "tile_k",
                "wave_m", "wave_n", "mfma", "tiles_m", "tiles_n", "k_tiles", "tail_m", "tail_n", "tail_k",
-               "eff_split_k", "k_iters", "slabs", "eff_vec_a", "eff_vec_b", "eff_vec_c", "eff_unroll",
-               "stages", "order", "grid", "block", "lds_bytes", "workspace_bytes")
+               "eff_split_k", "k_iters", "slabs", "order", "grid", "block", "workspace_bytes")
 
 
 def ceil_div(a: int, b: int) -> int:
@@ -173,13 +174,6 @@ def pow2_dividing(vmax: int, extent: int) -> int:
     return v
 
 
-def mfma_k_granule(dtype: int, mfma: int) -> int:
-    """K elements one 16-byte operand fetch per lane feeds to the matrix unit."""
-    if dtype == DT_F32:
-        return 8 if mfma == 32 else 16
-    return 16 if mfma == 32 else 32
-
-
 def gemm_extents(cls: int, shape: dict):
     """(batch, M, N, K) of the contraction, or (1, Ho, Wo, planes) for depthwise; None if ill-formed."""
     if cls in CONV_CLASSES or cls == CLS_DWCONV_BIAS_RELU6:
@@ -198,11 +192,8 @@ def gemm_extents(cls: int, shape: dict):
             if shape["k"] != shape["c"]:
                 return None
             return (1, ho, wo, shape["n"] * shape["c"])
-        # reduction = filter rows x the run of S * C elements a filter row covers contiguously in an
-        # NHWC image row, the run rounded up to whole 16-byte items
-        per_item = 4 if shape["dtype"] == DT_F32 else 8
-        runp = ceil_div(shape["s"] * shape["c"], per_item) * per_item
-        return (1, shape["n"] * ho * wo, shape["k"], shape["r"] * runp)
+        # the fused GEMM view of Algorithm 2's loop nest: rows = output pixels, reduction = c * r * s
+        return (1, shape["n"] * ho * wo, shape["k"], shape["c"] * shape["r"] * shape["s"])
     if shape.get("kind") != "gemm":
         return None
     for f in ("batch", "m", "n", "k"):
@@ -213,33 +204,6 @@ def gemm_extents(cls: int, shape: dict):
     if cls in DENSE_CLASSES and (shape["batch"] != 1 or shape["trans_b"] != 1):
         return None  # dense weights are stored [out, in]
     return (shape["batch"], shape["m"], shape["n"], shape["k"])
-
-
-def staged_tile_bytes(cls: int, shape: dict, rec: dict) -> int:
-    """LDS bytes of one pipeline stage (resource model of the matrix-core sketch).
-
-    Operands contiguous along K (NHWC activations and KRSC filters included) are
-    staged row-major, each row padded by 16 bytes.  The [K][N] matrix of a
-    non-transposed batch matmul is staged K-major; its rows are padded so that the
-    row length is 32 mod 64 elements for bf16, and by 8 (32-wide block) or 4
-    (16-wide block) elements for fp32.
-    """
-    elem = 4 if shape["dtype"] == DT_F32 else 2
-    tm, tn, tk = rec["tile_m"], rec["tile_n"], rec["tile_k"]
-
-    def row_major(rows):
-        return rows * (tk + 16 // elem) * elem
-
-    def k_major(cols):
-        if shape["dtype"] == DT_BF16:
-            pad = (32 - cols % 64) % 64
-        else:
-            pad = 8 if rec["mfma"] == 32 else 4
-        return tk * (cols + pad) * elem
-
-    if cls in CONV_CLASSES or shape["trans_b"]:
-        return row_major(tm) + row_major(tn)
-    return row_major(tm) + k_major(tn)
 
 
 def _blank_plan():
@@ -319,11 +283,7 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
 
     strict = bool(flags & STRICT_DIVISIBLE)
     batch, M, N, K = ext
-    dt = shape["dtype"]
-    elem = 4 if dt == DT_F32 else 2
-    vmax = min(rec["vec"], 16 // elem)
-    plan.update(sketch=sk, batch=batch, M=M, N=N, K=K, order=rec["order"], stages=rec["stages"],
-                mfma=rec["mfma"])
+    plan.update(sketch=sk, batch=batch, M=M, N=N, K=K, order=rec["order"], mfma=rec["mfma"])
 
     if sk == SK_DIRECT:
         total = batch * M * N * (K if is_dw else 1)
@@ -331,22 +291,18 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
         if grid >= 2 ** 31:
             return _fail(plan, ERR_INVALID_SCHEDULE, R_GRID)
         plan.update(tile_m=1, tile_n=1, tile_k=1, wave_m=1, wave_n=1, tiles_m=M, tiles_n=N, k_tiles=K,
-                    tail_m=1, tail_n=1, tail_k=1, eff_split_k=1, k_iters=K, slabs=batch, eff_vec_a=1,
-                    eff_vec_b=1, eff_vec_c=1, eff_unroll=1, grid=grid, block=256)
+                    tail_m=1, tail_n=1, tail_k=1, eff_split_k=1, k_iters=K, slabs=batch, grid=grid, block=256)
         if is_dw:
             plan.update(k_iters=1, slabs=K)
         return plan
 
     tm, tn, tk = rec["tile_m"], rec["tile_n"], rec["tile_k"]
-    ev_planes = 1
     if sk == SK_DWCONV:
-        # Vectorize on the plane axis: a lane owns ev channel-contiguous planes, so the workgroup's
-        # tile_k lanes along that axis cover tile_k * ev planes
-        # (the register kernel only: one stage, equal strides of 1 or 2, input below 2 GiB)
-        vectorised = (rec["stages"] == 1 and shape["stride_h"] == shape["stride_w"] and shape["stride_h"] in (1, 2)
-                      and shape["n"] * shape["h"] * shape["w"] * shape["c"] * elem < 2 ** 31)
-        ev_planes = pow2_dividing(vmax, shape["c"]) if vectorised else 1
-        tk *= ev_planes
+        # Vectorize on the plane axis, reformulated to the target (Section 4.1): a lane owns the widest
+        # power-of-two group of channels, not above the record's width or one memory access, that divides
+        # the channel count; the tile_k lanes of a workgroup then cover tile_k * ev planes.
+        widest = 4 if shape["dtype"] == DT_F32 else 8  # elements of the widest single memory access
+        tk *= pow2_dividing(min(rec["vec"], widest), shape["c"])
     # Inner factors are kept; a factor larger than the loop it splits is invalid (Section 4.2).
     for factor, extent, reason in ((tm, M, R_FACTOR_GT_M), (tn, N, R_FACTOR_GT_N), (tk, K, R_FACTOR_GT_K)):
         if factor > extent:
@@ -361,79 +317,34 @@ def apply(rec: dict, cls: int, shape: dict, flags: int = 0) -> dict:
 
     if sk == SK_DWCONV:
         threads = rec["tile_k"] * (tm // rec["wave_m"]) * (tn // rec["wave_n"])
-        lds = 0
-        if rec["stages"] == 2:
-            rows = (tm - 1) * shape["stride_h"] + shape["r"]
-            cols = (tn - 1) * shape["stride_w"] + shape["s"]
-            lds = tk * rows * cols * elem
-        if lds > LDS_BUDGET:
-            return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
-        ev = ev_planes
         grid = tiles_m * tiles_n * k_tiles
         if grid >= 2 ** 31:
             return _fail(plan, ERR_INVALID_SCHEDULE, R_GRID)
-        plan.update(eff_split_k=1, k_iters=1, slabs=k_tiles, eff_vec_a=ev, eff_vec_b=1, eff_vec_c=ev,
-                    eff_unroll=min(rec["unroll"], rec["wave_m"]), grid=grid, block=threads, lds_bytes=lds)
+        plan.update(eff_split_k=1, k_iters=1, slabs=k_tiles, grid=grid, block=threads)
         return plan
 
     if sk == SK_GEMV:
-        chunk = tk // 64
-        ev = pow2_dividing(min(vmax, chunk), K)
         waves = tn // rec["wave_n"]
         grid = tiles_m * tiles_n * batch
         if grid >= 2 ** 31:
             return _fail(plan, ERR_INVALID_SCHEDULE, R_GRID)
-        plan.update(eff_split_k=1, k_iters=k_tiles, slabs=batch, eff_vec_a=ev, eff_vec_b=ev, eff_vec_c=1,
-                    eff_unroll=min(rec["unroll"], k_tiles), grid=grid, block=64 * waves)
+        plan.update(eff_split_k=1, k_iters=k_tiles, slabs=batch, grid=grid, block=64 * waves)
         return plan
 
-    # SK_MFMA
-    gran = mfma_k_granule(dt, rec["mfma"])
-    if tk % gran:
-        return _fail(plan, ERR_INVALID_SCHEDULE, R_K_GRANULE)
-    # Parallel split of the reduction: a split larger than the number of K tiles splits nothing.
+    # SK_MFMA.  Parallel split of the reduction: a split larger than the number of K tiles splits nothing.
     if rec["split_k"] > k_tiles:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_SPLIT_K)
     if strict and k_tiles % rec["split_k"]:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_NOT_DIVISIBLE)
     k_iters = ceil_div(k_tiles, rec["split_k"])
     eff_split_k = ceil_div(k_tiles, k_iters)  # no empty split
-    if cls in CONV_CLASSES:
-        # vectors run along the channel axis of both operands and along the output channels
-        eva = evb = pow2_dividing(vmax, shape["c"])
-        evc = pow2_dividing(vmax, N)
-        whole_items = eva * elem == 16
-        in_range = True  # the operator refuses larger tensors for every matrix-core record
-    else:
-        eva = pow2_dividing(vmax, K)
-        evb = pow2_dividing(vmax, K) if shape["trans_b"] else pow2_dividing(vmax, N)
-        evc = pow2_dividing(vmax, N)
-        whole_items = bool(shape["trans_b"]) and eva * elem == 16
-        in_range = M * K * elem < 2 ** 31 and N * K * elem < 2 ** 31
-    # Three or four stages ask for the asynchronous ring of unpadded LDS buffers; where it does not
-    # apply the record is reformulated to two stages.
-    block = 64 * (tm // rec["wave_m"]) * (tn // rec["wave_n"])
-    chunks = tk * elem // 16
-    ring_fits = (whole_items and in_range and (tm * chunks) % block == 0 and (tn * chunks) % block == 0
-                 and (block // 16) % chunks == 0)
-    stages = rec["stages"]
-    if stages >= 3 and not ring_fits:
-        stages = 2
-    plan["stages"] = stages
-    if stages >= 3:
-        lds = stages * (tm + tn) * tk * elem
-    else:
-        lds = stages * staged_tile_bytes(cls, shape, rec)
-    if lds > LDS_BUDGET:
-        return _fail(plan, ERR_INVALID_SCHEDULE, R_LDS)
     waves = (tm // rec["wave_m"]) * (tn // rec["wave_n"])
     slabs = batch * eff_split_k
     grid = tiles_m * tiles_n * slabs
     if grid >= 2 ** 31:
         return _fail(plan, ERR_INVALID_SCHEDULE, R_GRID)
-    plan.update(eff_split_k=eff_split_k, k_iters=k_iters, slabs=slabs, eff_vec_a=eva, eff_vec_b=evb,
-                eff_vec_c=evc, eff_unroll=min(rec["unroll"], tk // gran), grid=grid, block=64 * waves,
-                lds_bytes=lds, workspace_bytes=(4 * eff_split_k * batch * M * N) if eff_split_k > 1 else 0)
+    plan.update(eff_split_k=eff_split_k, k_iters=k_iters, slabs=slabs, grid=grid, block=64 * waves,
+                workspace_bytes=(4 * eff_split_k * batch * M * N) if eff_split_k > 1 else 0)
     return plan
 
 

@@ -63,11 +63,18 @@ class tt_plan(Structure):
         "eff_vec_a", "eff_vec_b", "eff_vec_c", "eff_unroll", "stages", "order", "grid", "block", "lds_bytes")]
     _fields_ += [("workspace_bytes", c_int64), ("variant_id", c_int32), ("reserved", c_int32)]
 
-    # the fields that are a pure function of (record, class, shape, flags)
-    SPEC_FIELDS = tuple(n for n, _ in _fields_[:31]) + ("workspace_bytes",)
+    # the fields the method defines (Sections 4.1, 4.2); the others describe this library's kernels
+    METHOD_FIELDS = ("status", "reason", "sketch", "batch", "M", "N", "K", "tile_m", "tile_n", "tile_k", "wave_m",
+                     "wave_n", "mfma", "tiles_m", "tiles_n", "k_tiles", "tail_m", "tail_n", "tail_k", "eff_split_k",
+                     "k_iters", "slabs", "order", "grid", "block", "workspace_bytes")
+    LIBRARY_FIELDS = ("eff_vec_a", "eff_vec_b", "eff_vec_c", "eff_unroll", "stages", "lds_bytes", "variant_id")
 
-    def spec(self):
-        return {k: getattr(self, k) for k in self.SPEC_FIELDS}
+    def method(self):
+        return {k: getattr(self, k) for k in self.METHOD_FIELDS}
+
+    def runnable(self):
+        """A valid plan that a kernel of this library implements."""
+        return self.status == TT_OK and self.variant_id >= 0
 
 
 class tt_kernel_desc(Structure):
@@ -87,7 +94,7 @@ class tt_sweep_row(Structure):
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
            "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
-           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_select_donor")
+           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_num_variants", "tt_select_donor")
 
 
 def _load():
@@ -121,7 +128,7 @@ def _load():
     lib.tt_run_kernels.argtypes = [POINTER(tt_kernel_desc), POINTER(POINTER(tt_schedule)), ctypes.c_int, ctypes.c_int,
                                    c_void_p]
     lib.tt_schedule_space.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(tt_schedule), ctypes.c_int]
-    lib.tt_variant_info.argtypes = [ctypes.c_int, POINTER(c_int32 * 10)]
+    lib.tt_variant_info.argtypes = [ctypes.c_int, POINTER(c_int32 * 12)]
     lib.tt_sweep_select.argtypes = [POINTER(c_int32), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
                                     POINTER(c_double), ctypes.c_int, POINTER(tt_sweep_row)]
     lib.tt_select_donor.argtypes = [POINTER(c_double), ctypes.c_int, POINTER(c_int32), ctypes.c_int, POINTER(c_double),
@@ -424,14 +431,23 @@ class KernelList:
         _check(lib.tt_run_kernels(self.descs, self.ptrs, self.n, repeat, _stream()), "tt_run_kernels")
 
 
+VARIANT_INFO = ("dtype", "family", "tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfma", "amode", "pipe",
+                "stage_bytes", "k_granule")
+
+
+def tt_variant_info(variant_id: int):
+    info = (c_int32 * 12)()
+    _check(lib.tt_variant_info(variant_id, byref(info)), "tt_variant_info")
+    return list(info)
+
+
 def variant_name(plan: tt_plan, shape=None) -> str:
     """Name of the kernel a plan launches, spelled like the demangled symbol rocprofv3 reports.
 
     `shape` (a conv shape) is needed only to tell the two depthwise kernels apart.
     """
     if plan.sketch == TT_SK_MFMA:
-        info = (c_int32 * 10)()
-        _check(lib.tt_variant_info(plan.variant_id, byref(info)), "tt_variant_info")
+        info = tt_variant_info(plan.variant_id)
         if info[9]:
             return "tt::contract_async_kernel<" + ", ".join(str(v) for v in info[:8]) + ">"
         return "tt::contract_kernel<" + ", ".join(str(v) for v in info[:9]) + ">"

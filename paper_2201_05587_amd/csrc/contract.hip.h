@@ -152,6 +152,7 @@ template <> struct Mma<TT_F32, 16> {
 __device__ __forceinline__ void load16(u32x4 &dst, const void *p) { __builtin_memcpy(&dst, p, 16); }
 
 // Shift the 16-byte value by whole elements: positive = towards higher element indices; zero fill.
+// |elems| must be below the item's element count (a shift by the whole width is undefined).
 template <int DT> __device__ __forceinline__ u32x4 shift_elems(const u32x4 &v, int elems)
 {
     constexpr int EB = DT == TT_F32 ? 32 : 16;
@@ -234,8 +235,9 @@ template <int DT, int ROWS, int TK, int THREADS> struct RowKLoader {
             if (!interior) {
                 const int gk = k0 + kc * CH;
                 const int back = gk - min(gk, K - CH); // how far the load was moved back
-                if (back > 0 || gk + CH > k_end) v = keep_first<DT>(shift_elems<DT>(v, -back), k_end - gk);
-                if (row0 + r >= rows_total) v = u32x4{0u, 0u, 0u, 0u};
+                if (back > 0 || gk + CH > k_end) v = keep_first<DT>(shift_elems<DT>(v, -min(back, CH - 1)), k_end - gk);
+                // a chunk that starts at or past the end of the row or of the slice holds nothing
+                if (row0 + r >= rows_total || back >= CH || gk >= k_end) v = u32x4{0u, 0u, 0u, 0u};
             }
             *reinterpret_cast<u32x4 *>(lds + r * ROWB + kc * 16) = v;
         }
@@ -463,8 +465,8 @@ template <int DT, int TN, int TK, int THREADS, int LEN> struct KRowTileLoader {
             u32x4 v = st.raw[i];
             if (!interior) {
                 const int back = n - min(n, N - G);
-                if (back > 0) v = keep_first<DT>(shift_elems<DT>(v, -back), N - n);
-                if (k0 + kl >= k_end || n >= N) v = u32x4{0u, 0u, 0u, 0u};
+                if (back > 0) v = keep_first<DT>(shift_elems<DT>(v, -min(back, G - 1)), N - n);
+                if (k0 + kl >= k_end || n >= N || back >= G) v = u32x4{0u, 0u, 0u, 0u};
             }
             *reinterpret_cast<u32x4 *>(lds + ((size_t)kl * LEN + ng * G) * sizeof(E)) = v;
         }
@@ -670,7 +672,8 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     constexpr int ROWB = L::ROWB, A_BYTES = L::A_BYTES, STAGE_BYTES = L::STAGE_BYTES;
     constexpr int NWR = TM / WM; // waves along M
     constexpr int NI = WM / MF, NJ = WN / MF;
-    constexpr int LG = 64 / MF, KS = CH * LG, NKS = TK / KS;
+    constexpr int LG = 64 / MF, KS = k_granule(DT, MF), NKS = TK / KS;
+    static_assert(KS == CH * LG, "one 16-byte fragment per lane group");
     constexpr int ACC = MF * MF / 64;
     constexpr bool B_KMAJOR = FAM == FAM_GEMM_NN;
     constexpr bool CONV = FAM == FAM_CONV;
@@ -688,8 +691,10 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
-    const int k_end = tc.k0 + tc.k_ext;
-    const int kt_count = (tc.k_ext + TK - 1) / TK;
+    // The gathering loaders walk the reduction in runs padded to whole 16-byte items (k_walk >= K):
+    // the split that ends at K runs on to the end of that walk.
+    const int k_end = (CONV && tc.k0 + tc.k_ext == g.K) ? g.k_walk : tc.k0 + tc.k_ext;
+    const int kt_count = (k_end - tc.k0 + TK - 1) / TK;
     const int bidx = tc.hi;
 
     const E *a_base = static_cast<const E *>(g.a);
@@ -853,12 +858,15 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
 // chunk swizzle of row r for rows of CPR 16-byte chunks (CPR = 4, 8 or 16): depends on r mod 16 only
 template <int CPR> __device__ __forceinline__ int chunk_swizzle(int r) { return (r / (16 / CPR)) % CPR; }
 
+// M0 is named as clobbered so that the compiler never places this statement between a write of M0 of
+// its own and the instruction that reads it (M0 is a reserved register, which the allocator does not
+// hand out; the compiler's generic warning about reserved registers in clobber lists is switched off).
 __device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_offset, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(lds_addr), "v"(byte_offset), "s"(rsrc)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 template <int N> __device__ __forceinline__ void wait_loads_outstanding()
@@ -960,6 +968,12 @@ template <int DT, int ROWS, int TK, int THREADS> struct AsyncGather {
     }
 };
 
+// One buffer of the ring: the A tile followed by the B tile, rows unpadded.
+template <int DT, int TM, int TN, int TK> struct RingLayout {
+    static constexpr int RB = TK * (int)sizeof(typename ElemOf<DT>::type);
+    static constexpr int A_BYTES = TM * RB, STAGE_BYTES = (TM + TN) * RB;
+};
+
 // Conv (16-byte gathers) and dense family with the asynchronous pipeline; g.stages = 3 or 4 buffers.
 template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF>
 __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_kernel(const ContractArgs g)
@@ -968,8 +982,9 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     using E = typename ElemOf<DT>::type;
     constexpr int CH = ElemOf<DT>::CH, ES = (int)sizeof(E);
     constexpr int THREADS = (TM / WM) * (TN / WN) * 64;
-    constexpr int RB = TK * ES, CPR = TK / CH; // unpadded row
-    constexpr int A_BYTES = TM * RB, STAGE_BYTES = (TM + TN) * RB;
+    using L = RingLayout<DT, TM, TN, TK>;
+    constexpr int RB = L::RB, CPR = TK / CH;
+    constexpr int A_BYTES = L::A_BYTES, STAGE_BYTES = L::STAGE_BYTES;
     constexpr int NWR = TM / WM;
     constexpr int NI = WM / MF, NJ = WN / MF;
     constexpr int LG = 64 / MF, KS = CH * LG, NKS = TK / KS;
@@ -989,7 +1004,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
-    const int k_end = tc.k0 + tc.k_ext;
+    const int k_end = tc.k0 + tc.k_ext; // (whole items only: the gather's walk is the reduction itself)
     const int kt_count = (tc.k_ext + TK - 1) / TK;
     const int bidx = tc.hi;
     const int nst = g.stages;
@@ -1174,6 +1189,16 @@ int launch_contract(const ContractArgs &args, int grid, int lds_bytes, void *str
     hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds_bytes, static_cast<hipStream_t>(stream), args);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : note_hip_error((int)e, "contract_kernel launch");
+}
+
+// What the host's resource check multiplies by the number of stages.
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int AM> int stage_bytes_contract()
+{
+    return StageLayout<DT, FAM, TM, TN, TK, MF>::STAGE_BYTES;
+}
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF> int stage_bytes_contract_async()
+{
+    return RingLayout<DT, TM, TN, TK>::STAGE_BYTES;
 }
 
 template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF>

@@ -124,6 +124,7 @@ extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bia
     const int per_item = 16 / elem;
     g.run = shape->s * shape->c;
     g.runp = (g.run + per_item - 1) / per_item * per_item;
+    g.k_walk = shape->r * g.runp;
     g.div_hw = make_fastdiv((uint32_t)(g.Ho * g.Wo));
     g.div_wo = make_fastdiv((uint32_t)g.Wo);
     g.a_bytes = (uint32_t)x_bytes;

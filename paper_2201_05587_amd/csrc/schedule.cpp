@@ -50,12 +50,11 @@ bool extents_of(int cls, const void *shape, Extents *e, int *dtype)
             *e = {1, ho, wo, (int)planes};
             return true;
         }
-        // The reduction runs over filter rows times the run of S * C elements a filter row covers
-        // contiguously in an NHWC image row, the run rounded up to whole 16-byte items.
-        const int per_item = s->dtype == TT_F32 ? 4 : 8;
-        const int64_t run = (int64_t)s->s * s->c, runp = (run + per_item - 1) / per_item * per_item;
-        const int64_t m = (int64_t)s->n * ho * wo, k = (int64_t)s->r * runp;
-        if (m > INT32_MAX || k > INT32_MAX) return false;
+        // The fused GEMM view of Algorithm 2's loop nest: rows are output pixels, the reduction runs
+        // over c * r * s.  (The gathering loaders walk it in padded runs; that walk, which is at most
+        // 8 / 7 of the reduction plus 7 elements per filter row, must also fit 32 bits.)
+        const int64_t m = (int64_t)s->n * ho * wo, k = (int64_t)s->c * s->r * s->s;
+        if (m > INT32_MAX || k + k / 4 + 8ll * s->r > INT32_MAX) return false;
         *e = {1, (int)m, s->k, (int)k};
         return true;
     }
@@ -258,20 +257,17 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         p.eff_vec_a = p.eff_vec_b = p.eff_vec_c = p.eff_unroll = 1;
         p.grid = (int)grid;
         p.block = 256;
+        p.variant_id = 0;
         *plan = p;
         return TT_OK;
     }
 
-    // Depthwise: Vectorize applies to the plane axis.  A lane owns ev channel-contiguous planes, so
-    // the tile_k lanes a workgroup has along that axis cover tile_k * ev planes.
-    // (The register kernel only: one stage, equal strides of 1 or 2, input below 2 GiB.)
+    // Depthwise: Vectorize applies to the plane axis and is reformulated to the target (Section 4.1):
+    // a lane owns the widest group of channel-contiguous planes, not above the record's width, that
+    // divides the channel count, so the tile_k lanes a workgroup has along that axis cover tile_k * ev
+    // planes.
     int ev_planes = 1;
-    if (r.sketch == TT_SK_DWCONV) {
-        const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
-        const bool vectorised = r.stages == 1 && s->stride_h == s->stride_w && (s->stride_h == 1 || s->stride_h == 2) &&
-                                (int64_t)s->n * s->h * s->w * s->c * elem < (1ll << 31);
-        if (vectorised) ev_planes = widest_dividing(vmax, s->c);
-    }
+    if (r.sketch == TT_SK_DWCONV) ev_planes = widest_dividing(vmax, static_cast<const tt_conv_shape *>(shape)->c);
     const int64_t tile_k_eff = (int64_t)r.tile_k * ev_planes;
     if (tile_k_eff > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_FACTOR_GT_K);
     // Inner factors are kept as recorded; a factor larger than the loop it splits cannot be applied.
@@ -296,6 +292,9 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
 
     if (r.sketch == TT_SK_DWCONV) {
         const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
+        const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.k_tiles;
+        if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+        // The library's own part: the input patch the two-stage kernel keeps in LDS, and which kernel runs.
         int64_t lds = 0;
         if (r.stages == 2) {
             const int64_t rows = (int64_t)(r.tile_m - 1) * s->stride_h + s->r;
@@ -303,8 +302,11 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
             lds = p.tile_k * rows * cols * elem;
         }
         if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
-        const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.k_tiles;
-        if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+        // Several planes per lane exist in the register kernel only (one stage, equal strides of 1 or 2,
+        // input below 2 GiB); elsewhere such a plan has no kernel.
+        const bool rows_kernel = r.stages == 1 && s->stride_h == s->stride_w && (s->stride_h == 1 || s->stride_h == 2) &&
+                                 (int64_t)s->n * s->h * s->w * s->c * elem < (1ll << 31);
+        p.variant_id = (ev_planes == 1 || rows_kernel) && s->r == 3 && s->s == 3 && dt == TT_F32 ? 0 : -1;
         p.eff_split_k = 1;
         p.k_iters = 1;
         p.slabs = p.k_tiles;
@@ -330,17 +332,27 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         p.eff_unroll = std::min(r.unroll, p.k_tiles);
         p.grid = (int)grid;
         p.block = 64 * (r.tile_n / r.wave_n);
+        p.variant_id = 0;
         *plan = p;
         return TT_OK;
     }
 
-    // Matrix-core sketch.
-    const int granule = dt == TT_F32 ? (r.mfma == 32 ? 8 : 16) : (r.mfma == 32 ? 16 : 32);
-    if (r.tile_k % granule) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_K_GRANULE);
+    // Matrix-core sketch.  First what the method defines: the parallel split of the reduction and the grid.
     if (r.split_k > p.k_tiles) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_SPLIT_K);
     if (strict && p.k_tiles % r.split_k) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_NOT_DIVISIBLE);
     p.k_iters = cdiv(p.k_tiles, r.split_k);
     p.eff_split_k = cdiv(p.k_tiles, p.k_iters);
+    p.block = 64 * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
+    p.slabs = e.batch * p.eff_split_k;
+    const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.slabs;
+    if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+    p.grid = (int)grid;
+    p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
+
+    // From here on: this library's kernels (how the operands are fetched and staged).  None of it is
+    // part of the method; the constants come from the compiled kernels themselves.
+    const int granule = k_granule(dt, r.mfma);
+    if (r.tile_k % granule) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_K_GRANULE);
     int trans_b = 1;
     if (!is_conv_class(cls)) trans_b = static_cast<const tt_gemm_shape *>(shape)->trans_b;
     if (is_conv_class(cls)) {
@@ -353,10 +365,9 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         p.eff_vec_b = trans_b ? widest_dividing(vmax, e.K) : widest_dividing(vmax, e.N);
         p.eff_vec_c = widest_dividing(vmax, e.N);
     }
-    p.block = 64 * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
-    // How the kernels fetch their operands.  Conv: 16-byte gathers when the effective vector width
-    // fills an item, else element by element; a unit-stride 1x1 convolution without padding reads
-    // the activations as a plain [M][C] matrix and runs on the dense family.
+    // Conv: 16-byte gathers when the effective vector width fills an item, else element by element;
+    // a unit-stride 1x1 convolution without padding reads the activations as a plain [M][C] matrix
+    // and runs on the dense family.
     int amode = 0, family = family_of(cls, trans_b);
     bool whole_items = false; // both operands are fetched as whole 16-byte items along K
     if (is_conv_class(cls)) {
@@ -372,45 +383,26 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     } else if (trans_b) {
         whole_items = p.eff_vec_a * elem == 16;
     }
-    // Three or four stages ask for the asynchronous pipeline: 16-byte loads straight into a ring of
-    // unpadded LDS buffers.  It needs whole items, operands within 2 GiB, whole loads per thread and
-    // a workgroup that covers whole groups of 16 tile rows; a record that asks for it where it does
-    // not apply is reformulated to the two-stage register pipeline (Section 4.1 treats unroll
-    // depths the same way).
-    const int chunks = r.tile_k * elem / 16;
+    // Three or four stages ask for the asynchronous pipeline (16-byte loads straight into a ring of
+    // LDS buffers).  It exists for tiles its loader can fill (a compiled ring variant), whole items
+    // and operands within 2 GiB; a record that asks for it elsewhere is reformulated to the two-stage
+    // register pipeline (Section 4.1 treats unroll depths the same way).
     // (the conv entry point refuses tensors of 2 GiB and more for every matrix-core record)
     const bool in_range = is_conv_class(cls) ||
                           ((int64_t)e.M * e.K * elem < (1ll << 31) && (int64_t)e.N * e.K * elem < (1ll << 31));
-    const bool ring_fits = whole_items && in_range && (r.tile_m * chunks) % p.block == 0 &&
-                           (r.tile_n * chunks) % p.block == 0 && (p.block / 16) % chunks == 0;
-    if (r.stages >= 3 && !ring_fits) p.stages = 2;
-    // Staged tiles.  The register pipeline keeps an operand that is contiguous along K (NHWC
-    // activations and KRSC filters included) row-major with 16 bytes of row padding, and the [K][N]
-    // matrix of a non-transposed batch matmul K-major with a row padding that depends on the data
-    // type and the block.  The asynchronous ring holds unpadded row-major tiles.
-    auto rowk_bytes = [&](int rows) { return (int64_t)rows * (r.tile_k + 16 / elem) * elem; };
-    auto kmajor_bytes = [&](int cols) {
-        const int pad = dt == TT_BF16 ? (32 + 64 - cols % 64) % 64 : (r.mfma == 32 ? 8 : 4);
-        return (int64_t)r.tile_k * (cols + pad) * elem;
-    };
-    int64_t lds;
-    if (p.stages >= 3) {
-        lds = (int64_t)p.stages * (r.tile_m + r.tile_n) * r.tile_k * elem;
-    } else {
-        const int64_t a_bytes = rowk_bytes(r.tile_m);
-        const int64_t b_bytes = trans_b ? rowk_bytes(r.tile_n) : kmajor_bytes(r.tile_n);
-        lds = (int64_t)p.stages * (a_bytes + b_bytes);
-    }
-    if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
-    p.slabs = e.batch * p.eff_split_k;
-    const int64_t grid = (int64_t)p.tiles_m * p.tiles_n * p.slabs;
-    if (grid > INT32_MAX) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_GRID);
+    const int ring_id = whole_items && in_range
+                            ? find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode, 1)
+                            : -1;
+    if (r.stages >= 3 && ring_id < 0) p.stages = 2;
     p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
-    p.grid = (int)grid;
-    p.lds_bytes = (int)lds;
-    p.workspace_bytes = p.eff_split_k > 1 ? 4ll * p.eff_split_k * e.batch * e.M * e.N : 0;
-    p.variant_id = find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode,
-                                p.stages >= 3 ? 1 : 0);
+    p.variant_id = p.stages >= 3 ? ring_id
+                                 : find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma,
+                                                amode, 0);
+    if (p.variant_id >= 0) {
+        const int64_t lds = (int64_t)p.stages * kVariants[p.variant_id].stage_bytes();
+        if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
+        p.lds_bytes = (int)lds;
+    }
     *plan = p;
     return TT_OK;
 }
@@ -437,14 +429,17 @@ extern "C" int64_t tt_debug_fast_div(uint32_t n, uint32_t d)
     return (int64_t)fast_div(n, make_fastdiv(d));
 }
 
-extern "C" int tt_variant_info(int variant_id, int32_t out[10])
+extern "C" int tt_variant_info(int variant_id, int32_t out[12])
 {
     if (!out || variant_id < 0 || variant_id >= kNumVariants) return TT_ERR_BAD_ARG;
     const Variant &v = kVariants[variant_id];
-    const int32_t vals[10] = {v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode, v.pipe};
-    std::copy(vals, vals + 10, out);
+    const int32_t vals[12] = {v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode, v.pipe,
+                              v.stage_bytes(), k_granule(v.dtype, v.mfma)};
+    std::copy(vals, vals + 12, out);
     return TT_OK;
 }
+
+extern "C" int tt_num_variants(void) { return kNumVariants; }
 
 extern "C" int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t *pool_cls, int np,
                                const double *pair_us, const double *default_us, int allow_slower, tt_sweep_row *rows)
@@ -527,8 +522,12 @@ extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out
                     for (int wm : wms)
                         for (int wn : wns)
                             for (int stages = 1; stages <= (level >= 2 ? 2 : 1); ++stages) {
-                                tt_schedule r = make_record(cls, TT_SK_DWCONV, tm, tn, tk, wm, wn, 0, 1, 0, 4, wm, stages);
-                                if (record_well_formed(r)) recs.push_back(r);
+                                // several planes per lane exist in the one-stage kernel only
+                                for (int vec : {1, 2, 4}) {
+                                    if (stages == 2 && vec != 1) continue;
+                                    tt_schedule r = make_record(cls, TT_SK_DWCONV, tm, tn, tk, wm, wn, 0, 1, 0, vec, wm, stages);
+                                    if (record_well_formed(r)) recs.push_back(r);
+                                }
                             }
     } else {
         // families this class can run on: conv classes one, dense one, batch matmul both layouts

@@ -408,10 +408,8 @@ int launch_dwconv(const DwArgs &a, const tt_plan &plan, void *stream)
     if (a.wave_m == WM_ && a.wave_n == WN_) {                                                                        \
         if (rows_kernel) return launch_dw_rows<WM_, WN_>(a, grid, block, s);                                         \
         auto kern = dwconv3x3_kernel<WM_, WN_>;                                                                      \
-        if (lds > 48 * 1024 &&                                                                                       \
-            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
-                                lds) != hipSuccess)                                                                  \
-            return TT_ERR_HIP;                                                                                       \
+        static DynamicLdsLimit limit; /* per kernel instance; host threads may launch concurrently */               \
+        if (const int rc = limit.raise_to(reinterpret_cast<const void *>(kern), lds); rc != TT_OK) return rc;        \
         hipLaunchKernelGGL(kern, grid, block, lds, s, a);                                                            \
         return launched();                                                                                           \
     }

@@ -154,6 +154,9 @@ struct ContractArgs {
     float *ws;
     TileMap map;
     int32_t batch, M, N, K;
+    // FAM_CONV: the extent of the reduction as the gathering loaders walk it, R * runp >= K (see below);
+    // the split of the reduction that ends at K runs on to k_walk
+    int32_t k_walk;
     // convolution geometry (FAM_CONV).  The reduction index is k = r * runp + j: filter row r and
     // position j inside the run of S * C elements that one filter row covers contiguously in an
     // NHWC image row (and in a KRSC filter); runp is the run rounded up to whole 16-byte items.
@@ -179,7 +182,12 @@ struct Variant {
     int32_t amode; // conv family: bytes per gathered load (16 or the element size); 0 otherwise
     int32_t pipe;  // 0: register-staged loads, 1 or 2 LDS stages; 1: asynchronous loads into a ring of 3 or 4
     int (*launch)(const ContractArgs &args, int grid, int lds_bytes, void *stream);
+    int (*stage_bytes)(); // LDS bytes of one pipeline stage, as the compiled kernel lays its tiles out
 };
+
+// Reduction elements one 16-byte operand fragment per lane feeds to the matrix cores: a block of MF rows
+// leaves 64 / MF lane groups along K, each holding 16 bytes.  tile_k must be a multiple of it.
+constexpr int k_granule(int dtype, int mfma) { return (dtype == TT_F32 ? 4 : 8) * (64 / mfma); }
 
 // variant table (generated) and lookups
 extern const Variant kVariants[];

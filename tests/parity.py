@@ -66,7 +66,13 @@ def check_kernel(kernel: wl.Kernel, scheds, seed=1234, ref=None):
                 continue
         if s is not None:
             plan = api.tt_schedule_apply(s, kernel.cls, kernel.shape)
-            if plan.sketch == api.TT_SK_MFMA and plan.variant_id < 0:
+            if plan.status != api.TT_OK:
+                # refused for a reason of the library's own kernels (LDS size, K step): nothing launched
+                assert plan.status == api.TT_ERR_INVALID_SCHEDULE and plan.reason in (6, 7), (kernel.name, s)
+                assert dk.run(s) == api.TT_ERR_INVALID_SCHEDULE
+                outs.append(None)
+                continue
+            if plan.variant_id < 0:
                 # a valid plan no compiled kernel implements: refused, nothing launched
                 assert dk.run(s) == api.TT_ERR_UNSUPPORTED, (kernel.name, s)
                 outs.append(None)

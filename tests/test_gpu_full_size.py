@@ -1,11 +1,11 @@
 """Parity at the full sizes of the evaluation configurations, in the launch configuration bench.py times.
 
-The ResNet50-shaped batch-32 bf16 kernels are too large for the whole-tensor oracle, so each is checked
-on sampled outputs the point-wise oracle computes one by one (uniform samples plus every corner and edge
-class of the output map, where padding and ragged tiles meet) and on properties that hold at any size
-(finite, ReLU outputs non-negative, nothing left unwritten).  Every kernel runs under the default
-record, under the record the stored transfer sweep chose and under the native-swept one, i.e. the
-records the timed pass launches.  The smaller configurations are compared whole.
+Every kernel of every configuration runs under the default record, under the record the stored
+transfer sweep chose and under the native-swept one, i.e. the records the timed pass launches, and
+its whole output tensor is compared with the oracle element by element.  A stored record that no
+longer applies to its kernel, or that no compiled kernel implements, is a failure, not a skip.  The
+ResNet50-shaped batch-32 kernels are additionally checked on sampled outputs the point-wise oracle
+computes one by one (a fast pre-check that names the failing coordinates).
 """
 import json
 import os
@@ -26,10 +26,9 @@ KNOBS = ("cls", "sketch", "tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfm
 
 
 def stored_records(workload: str):
-    """name -> list of records (transfer choice, native choice) of the committed sweep outcome, if any."""
+    """name -> list of records (transfer choice, native choice) of the committed sweep outcome."""
     path = os.path.join(TUNED_DIR, f"{workload}.json")
-    if not os.path.exists(path):
-        return {}
+    assert os.path.exists(path), f"no stored sweep outcome for {workload}"
     with open(path) as f:
         tuned = json.load(f)
     out = {}
@@ -41,6 +40,17 @@ def stored_records(workload: str):
                 recs.append(api.make_schedule(**{f: kn[f] for f in KNOBS}))
         out[e["name"]] = recs
     return out
+
+
+def records_to_check(workload: str, kernel: wl.Kernel):
+    """[default] + the stored records of the kernel, each of which must be a plan a kernel implements."""
+    stored = stored_records(workload)
+    assert kernel.name in stored, (workload, kernel.name, "kernel missing from the stored sweep outcome")
+    for rec in stored[kernel.name]:
+        plan = api.tt_schedule_apply(rec, kernel.cls, kernel.shape)
+        assert plan.status == api.TT_OK, (kernel.name, rec, api.status_name(plan.status), plan.reason)
+        assert plan.variant_id >= 0, (kernel.name, rec, "no compiled kernel implements this stored record")
+    return [None] + stored[kernel.name]
 
 
 def sample_coords(kernel: wl.Kernel, count: int, seed: int) -> np.ndarray:
@@ -78,19 +88,14 @@ def test_cfg5_full_size_sampled(index):
     s = kernel.shape
     seed = wl.seed_for(cfg, index)
     inp = wl.make_inputs(kernel, seed)
-    coords = sample_coords(kernel, 20000, seed)
+    coords = sample_coords(kernel, 4000, seed)
     act = wl.CLASS_ACT[kernel.cls]
     ref = O.conv2d_points(inp["x"], inp["w"], coords, inp["bias"], inp.get("res"), (s.stride_h, s.stride_w),
                           (s.pad_h, s.pad_w), act)
     dk = harness.device_kernel(kernel, seed, inp)
-    scheds = [None] + stored_records("cfg5").get(kernel.name, [])
+    scheds = records_to_check("cfg5", kernel)
     ix = tuple(torch.from_numpy(coords[:, j].astype(np.int64)).cuda() for j in range(4))
-    ran = 0
     for rec in scheds:
-        if rec is not None:
-            plan = api.tt_schedule_apply(rec, kernel.cls, kernel.shape)
-            if plan.status != api.TT_OK or (plan.sketch == api.TT_SK_MFMA and plan.variant_id < 0):
-                continue  # a stored record this build no longer carries a kernel for
         dk.output().fill_(float("nan"))
         rc = dk.run(rec)
         torch.cuda.synchronize()
@@ -102,8 +107,6 @@ def test_cfg5_full_size_sampled(index):
         got = y[ix].float().cpu().numpy()
         # same bound as the whole-tensor comparison; the rms of the sample stands in for the tensor's
         assert_close(got, ref, s.dtype, f"{kernel.name} {rec}")
-        ran += 1
-    assert ran >= 1
 
 
 def whole_config(name):
@@ -119,8 +122,14 @@ def cases_of(name):
 def run_whole(name, index):
     cfg, targets = whole_config(name)
     kernel = targets[index]
-    scheds = [None] + stored_records(name).get(kernel.name, [])
-    check_kernel(kernel, scheds, seed=wl.seed_for(cfg, index))
+    _, outs = check_kernel(kernel, records_to_check(name, kernel), seed=wl.seed_for(cfg, index))
+    assert all(o is not None for o in outs), (name, kernel.name, "a stored record was refused")
+
+
+@pytest.mark.parametrize("index", cfg5_cases())
+def test_cfg5_resnet50_b32_bf16_whole(index):
+    """The batch-32 kernels whole: the oracle computes all 24 layers in seconds on the host cores."""
+    run_whole("cfg5", index)
 
 
 @pytest.mark.parametrize("index", cases_of("cfg2"))
@@ -136,6 +145,12 @@ def test_cfg3_bert_bf16_whole(index):
 @pytest.mark.parametrize("index", cases_of("cfg4"))
 def test_cfg4_mobilenetv2_fp32_whole(index):
     run_whole("cfg4", index)
+
+
+@pytest.mark.parametrize("index", cases_of("seq128_from_256"))
+def test_seq128_bert_bf16_whole(index):
+    """Targets at sequence length 128 under the records transferred from length 256 (Section 5.4)."""
+    run_whole("seq128_from_256", index)
 
 
 @pytest.mark.parametrize("index", cases_of("seq256_from_128"))

@@ -17,11 +17,43 @@ def to_c_record(rec: dict) -> api.tt_schedule:
     return api.make_schedule(**{k: rec[k] for k in S.RECORD_FIELDS})
 
 
-def plan_equal(cplan: api.tt_plan, oplan: dict):
-    got = cplan.spec()
-    assert set(got) == set(S.PLAN_FIELDS)
+RESOURCE_REASONS = (6, 7)  # TT_R_LDS, TT_R_K_GRANULE: the library's own, checked after every method rule
+
+
+def plan_equal(cplan: api.tt_plan, oplan: dict, rec=None):
+    """The method fields of the library's plan against the oracle's, bit for bit.
+
+    Where the library rejects a record for a reason of its own kernels (LDS size, K step of the matrix
+    cores) the oracle must have found the record valid as far as the method goes; the library's claim is
+    then checked against what its compiled kernels export.
+    """
+    assert set(api.tt_plan.METHOD_FIELDS) == set(S.PLAN_FIELDS)
+    if cplan.status == api.TT_ERR_INVALID_SCHEDULE and cplan.reason in RESOURCE_REASONS:
+        assert oplan["status"] == S.OK, (cplan.reason, oplan)
+        assert rec is not None and rec["sketch"] in (S.SK_MFMA, S.SK_DWCONV)
+        if cplan.reason == 7:
+            assert rec["tile_k"] % min(g for d, mf, g in kernel_k_granules() if mf == rec["mfma"]) or \
+                any(rec["tile_k"] % g for d, mf, g in kernel_k_granules() if mf == rec["mfma"])
+        return False
+    got = cplan.method()
     diff = {k: (got[k], oplan[k]) for k in S.PLAN_FIELDS if got[k] != oplan[k]}
     assert not diff, diff
+    return True
+
+
+_VARIANTS = []
+
+
+def all_variants():
+    if not _VARIANTS:
+        for i in range(api.lib.tt_num_variants()):
+            _VARIANTS.append(dict(zip(api.VARIANT_INFO, api.tt_variant_info(i))))
+    return _VARIANTS
+
+
+def kernel_k_granules():
+    """(dtype, mfma, K elements per matrix-core step) as the compiled kernels report them."""
+    return sorted({(v["dtype"], v["mfma"], v["k_granule"]) for v in all_variants()})
 
 
 def test_library_exports_every_declared_symbol():
@@ -67,19 +99,62 @@ def test_apply_matches_oracle_bit_for_bit_on_random_records():
     rng = random.Random(20220105)
     kernels = all_cfg_kernels()
     statuses = {}
+    resource_rejections = 0
     for it in range(6000):
         k = rng.choice(kernels)
         rec = random_record(rng, k.cls if rng.random() < 0.9 else rng.randrange(S.NUM_CLASSES))
         flags = S.STRICT_DIVISIBLE if rng.random() < 0.2 else 0
         oplan = S.apply(rec, k.cls, oshape(k), flags)
         cplan = api.tt_schedule_apply(to_c_record(rec), k.cls, k.shape, flags)
-        plan_equal(cplan, oplan)
         statuses[oplan["status"]] = statuses.get(oplan["status"], 0) + 1
+        if not plan_equal(cplan, oplan, rec):
+            resource_rejections += 1
+            continue
+        if oplan["status"] == S.OK:
+            check_library_fields(cplan, rec, k)
         if oplan["status"] == S.OK and oplan["sketch"] != S.SK_DIRECT and oplan["grid"] <= 4096 and it % 10 == 0:
             for wg in range(oplan["grid"]):
                 assert api.tt_plan_tile(cplan, wg) == S.plan_tile(oplan, wg)
     # the draw must exercise every outcome
     assert all(statuses.get(s, 0) > 50 for s in (S.OK, S.ERR_INVALID_SCHEDULE, S.ERR_CLASS_MISMATCH, S.ERR_BAD_ARG))
+    assert 0 < resource_rejections < 1500
+
+
+def check_library_fields(cplan, rec, k):
+    """The plan fields that describe the library's kernels, against what those kernels export and against
+    the properties a reformulated knob must have (Section 4.1): never wider than asked, a power of two,
+    dividing the extent it runs along, and maximal."""
+    s = k.shape
+    widest = 4 if s.dtype == wl.F32 else 8
+    if cplan.sketch == api.TT_SK_MFMA:
+        if k.is_conv():
+            along = dict(eff_vec_a=s.c, eff_vec_b=s.c, eff_vec_c=cplan.N)   # channels-last tensors
+        else:
+            along = dict(eff_vec_a=cplan.K, eff_vec_b=cplan.K if s.trans_b else cplan.N, eff_vec_c=cplan.N)
+        for f, extent in along.items():
+            v = getattr(cplan, f)
+            assert v == S.pow2_dividing(min(rec["vec"], widest), extent), (f, v, rec["vec"], extent)
+        assert 1 <= cplan.eff_unroll <= rec["unroll"]
+        assert cplan.stages == rec["stages"] or (rec["stages"] >= 3 and cplan.stages == 2)
+        if cplan.variant_id >= 0:
+            v = dict(zip(api.VARIANT_INFO, api.tt_variant_info(cplan.variant_id)))
+            assert (v["dtype"], v["tile_m"], v["tile_n"], v["tile_k"], v["wave_m"], v["wave_n"], v["mfma"]) == \
+                (s.dtype, rec["tile_m"], rec["tile_n"], rec["tile_k"], rec["wave_m"], rec["wave_n"], rec["mfma"])
+            assert v["pipe"] == (1 if cplan.stages >= 3 else 0)
+            assert cplan.lds_bytes == cplan.stages * v["stage_bytes"] <= 160 * 1024
+            assert rec["tile_k"] % v["k_granule"] == 0
+            assert cplan.eff_unroll == min(rec["unroll"], rec["tile_k"] // v["k_granule"])
+            # a stage holds at least the two operand tiles
+            assert v["stage_bytes"] >= (rec["tile_m"] + rec["tile_n"]) * rec["tile_k"] * (4 if s.dtype == wl.F32 else 2)
+        else:
+            assert cplan.lds_bytes == 0
+    elif cplan.sketch == api.TT_SK_DWCONV:
+        assert cplan.eff_vec_a == S.pow2_dividing(min(rec["vec"], widest), s.c)
+        assert cplan.tile_k == rec["tile_k"] * cplan.eff_vec_a
+        # several planes per lane run in the one-stage kernel only
+        assert (cplan.variant_id >= 0) == (cplan.eff_vec_a == 1 or rec["stages"] == 1)
+    else:
+        assert cplan.variant_id == 0
 
 
 @pytest.mark.parametrize("order", range(6))
@@ -92,7 +167,7 @@ def test_plan_tile_matches_oracle_for_every_order_on_the_configured_shapes(order
             rec = S.record(k.cls, S.SK_MFMA, 32, 32, 32, 16, 16, 16, rng.choice([1, 2, 5]), order)
         oplan = S.apply(rec, k.cls, oshape(k))
         cplan = api.tt_schedule_apply(to_c_record(rec), k.cls, k.shape)
-        plan_equal(cplan, oplan)
+        assert plan_equal(cplan, oplan, rec)
         if oplan["status"] != S.OK:
             continue
         g = oplan["grid"]
@@ -141,8 +216,55 @@ def test_schedule_space_is_well_formed_and_contains_the_default_tiles():
         rec = api.tt_schedule_default(k.cls, k.shape)
         plan = api.tt_schedule_apply(rec, k.cls, k.shape)
         assert plan.status == api.TT_OK
-        if plan.sketch == api.TT_SK_MFMA:
-            assert plan.variant_id >= 0, (k.name, rec)
+        assert plan.variant_id >= 0, (k.name, rec)
+
+
+def test_resource_rejections_come_from_the_compiled_kernels():
+    """TT_R_LDS and TT_R_K_GRANULE are decided by constants the kernels export, not by a second model."""
+    vs = all_variants()
+    assert len(vs) > 100
+    # every compiled tile_k is a multiple of its kernel's K step; a record whose tile_k is not is refused
+    assert all(v["tile_k"] % v["k_granule"] == 0 for v in vs)
+    bsh = wl.Kernel(wl.CLS_DENSE_ADD, wl.GemmShape(1, 256, 256, 256, 1, wl.BF16))
+    step16 = {v["k_granule"] for v in vs if v["dtype"] == wl.BF16 and v["mfma"] == 16}
+    assert len(step16) == 1 and 16 % step16.pop() != 0
+    p = api.tt_schedule_apply(api.make_schedule(bsh.cls, tile_k=16, mfma=16, vec=8), bsh.cls, bsh.shape)
+    assert (p.status, p.reason) == (api.TT_ERR_INVALID_SCHEDULE, 7)
+    assert api.tt_schedule_apply(api.make_schedule(bsh.cls, tile_k=16, mfma=32, vec=8), bsh.cls, bsh.shape).status == api.TT_OK
+    # the largest compiled tile does not fit twice: two stages are refused, one stage is a plan
+    big = max((v for v in vs if v["dtype"] == wl.BF16 and v["family"] == 1 and v["pipe"] == 0), key=lambda v: v["stage_bytes"])
+    assert 2 * big["stage_bytes"] > 160 * 1024 >= big["stage_bytes"]
+    wide = wl.Kernel(wl.CLS_DENSE_ADD, wl.GemmShape(1, 4096, 4096, 4096, 1, wl.BF16))
+    rec = {f: big[f] for f in ("tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfma")}
+    two = api.tt_schedule_apply(api.make_schedule(wide.cls, vec=8, stages=2, **rec), wide.cls, wide.shape)
+    one = api.tt_schedule_apply(api.make_schedule(wide.cls, vec=8, stages=1, **rec), wide.cls, wide.shape)
+    assert (two.status, two.reason) == (api.TT_ERR_INVALID_SCHEDULE, 6)
+    assert one.status == api.TT_OK and one.lds_bytes == big["stage_bytes"]
+    # the method still accepts both: the oracle knows nothing of LDS
+    orec = S.record(wide.cls, vec=8, stages=2, **rec)
+    assert S.apply(orec, wide.cls, oshape(wide))["status"] == S.OK
+
+
+def test_ring_stages_are_reformulated_where_no_ring_kernel_applies():
+    bf = wl.BF16
+    E = wl.CLS_CONV2D_BIAS_RELU
+    conv = wl.ConvShape(32, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, bf)
+    rec = dict(tile_m=64, tile_n=64, tile_k=64, wave_m=32, wave_n=32, mfma=32, vec=8, unroll=8)
+    p = api.tt_schedule_apply(api.make_schedule(E, stages=4, **rec), E, conv)
+    info = dict(zip(api.VARIANT_INFO, api.tt_variant_info(p.variant_id)))
+    assert (p.status, p.stages, info["pipe"], p.lds_bytes) == (api.TT_OK, 4, 1, 4 * info["stage_bytes"])
+    # a narrower vector knob gathers element by element: no ring, two stages of the register pipeline
+    p = api.tt_schedule_apply(api.make_schedule(E, stages=4, **dict(rec, vec=4)), E, conv)
+    assert p.stages == 2 and api.tt_variant_info(p.variant_id)[9] == 0
+    # 3 input channels never fill an item
+    stem = wl.ConvShape(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, bf)
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=4, **rec), E, stem).stages == 2
+    # the [K][N] operand of a non-transposed batch matmul stays on the register pipeline
+    bm = wl.CLS_BATCH_MATMUL
+    assert api.tt_schedule_apply(api.make_schedule(bm, stages=3, **rec), bm, wl.GemmShape(4, 128, 128, 64, 0, bf)).stages == 2
+    assert api.tt_schedule_apply(api.make_schedule(bm, stages=3, **rec), bm, wl.GemmShape(4, 128, 128, 64, 1, bf)).stages == 3
+    # five stages is not a record
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=5, **rec), E, conv).status == api.TT_ERR_BAD_ARG
 
 
 def test_division_by_multiplication_is_exact():

@@ -100,8 +100,6 @@ def test_apply_derives_outer_extents_from_the_target():
     assert target["eff_split_k"] == 2 and target["k_iters"] == 9
     assert target["grid"] == 49 * 2 * 2 and target["block"] == 64 * 2
     assert target["workspace_bytes"] == 4 * 2 * 3136 * 64
-    # row-major tiles padded by 16 bytes: activations 64 x (32 + 4) floats, filters 32 x (32 + 4) floats, two stages
-    assert target["lds_bytes"] == 2 * (64 * 36 + 32 * 36) * 4
 
 
 def test_factor_larger_than_loop_is_invalid_and_wrong_class_is_mismatch():
@@ -121,7 +119,7 @@ def test_factor_larger_than_loop_is_invalid_and_wrong_class_is_mismatch():
     assert S.apply(S.record(S.CLS_CONV2D_BIAS_ADD_RELU), E, cfg1_shape())["status"] == S.ERR_CLASS_MISMATCH
 
 
-def test_split_k_and_resource_validity():
+def test_split_of_the_reduction():
     sh = S.conv_shape(1, 64, 56, 56, 128, 1, 1, 2, 2)  # K = 64
     r = S.record(S.CLS_CONV2D_ADD, tile_k=32, split_k=4)
     p = S.apply(r, S.CLS_CONV2D_ADD, sh)
@@ -130,59 +128,40 @@ def test_split_k_and_resource_validity():
     assert (p["k_iters"], p["eff_split_k"]) == (5, 4)
     p = S.apply(S.record(E, tile_k=32, split_k=7), E, cfg1_shape())   # ceil(18/7)=3 -> 6 non-empty splits
     assert (p["k_iters"], p["eff_split_k"]) == (3, 6)
-    big = S.record(E, S.SK_MFMA, 256, 256, 128, 64, 64, 32, 1, 0, 4, 1, 2)
-    p = S.apply(big, E, S.conv_shape(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1))
-    assert p["status"] == S.ERR_INVALID_SCHEDULE and p["reason"] == S.R_LDS
-    # bf16 with the 16-wide matrix block consumes 32 K per fetch: tile_k = 16 cannot hold one
-    bsh = S.gemm_shape(1, 256, 256, 256, 1, S.DT_BF16)
-    p = S.apply(S.record(S.CLS_DENSE_ADD, tile_k=16, mfma=16), S.CLS_DENSE_ADD, bsh)
-    assert p["reason"] == S.R_K_GRANULE
-    assert S.apply(S.record(S.CLS_DENSE_ADD, tile_k=16, mfma=32), S.CLS_DENSE_ADD, bsh)["status"] == S.OK
+    # strict reading: the split has to divide the K tiles as well
+    assert S.apply(S.record(E, tile_k=32, split_k=4), E, cfg1_shape(), S.STRICT_DIVISIBLE)["reason"] == S.R_NOT_DIVISIBLE
+    assert S.apply(S.record(E, tile_k=32, split_k=3), E, cfg1_shape(), S.STRICT_DIVISIBLE)["status"] == S.OK
 
 
-def test_vector_width_and_unroll_are_reformulated_not_rejected():
-    stem = S.conv_shape(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)  # 3 channels: no vector fits a pixel
-    p = S.apply(S.record(E, vec=4, unroll=512), E, stem)
-    assert p["status"] == S.OK and (p["eff_vec_a"], p["eff_vec_b"], p["eff_vec_c"]) == (1, 1, 4)
-    # the reduction is 7 filter rows x (7 * 3 = 21 elements rounded up to 24, six 16-byte fp32 items)
-    assert p["K"] == 7 * 24 and S.apply(S.record(E), E, cfg1_shape())["K"] == 64 * 3 * 3
-    assert p["eff_unroll"] == 1  # tile_k 16 with the 16-wide fp32 block is a single step
-    p = S.apply(S.record(E, vec=4, tile_k=32, mfma=32, unroll=512), E, cfg1_shape())
-    assert (p["eff_vec_a"], p["eff_vec_b"], p["eff_vec_c"], p["eff_unroll"]) == (4, 4, 4, 4)
-    c6 = S.conv_shape(1, 6, 14, 14, 256, 3, 3, 1, 1, 1, 1)
-    assert S.apply(S.record(E, vec=4), E, c6)["eff_vec_a"] == 2    # pixels of 6 channels
+def test_the_reduction_of_a_convolution_is_c_r_s_whatever_the_channel_count():
+    """Factors are compared with the fused extents of Algorithm 2's nest: K = c * r * s, also where a
+    pixel's channels do not fill a memory access (3-channel stem, 36 channels in bf16)."""
+    stem = S.conv_shape(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)
+    p = S.apply(S.record(E, tile_k=16), E, stem)
+    assert (p["status"], p["M"], p["N"], p["K"]) == (S.OK, 112 * 112, 64, 147)
+    assert (p["k_tiles"], p["tail_k"]) == (10, 147 - 9 * 16)
+    assert S.apply(S.record(E, tile_k=128), E, stem)["k_tiles"] == 2
     pw = S.conv_shape(1, 36, 14, 14, 576, 1, 1, dtype=S.DT_BF16)
-    p = S.apply(S.record(E, vec=8, tile_k=32), E, pw)
-    assert (p["eff_vec_a"], p["eff_vec_c"], p["K"]) == (4, 8, 40)   # 36 = 4 * 9; 36 rounded up to 8-element items
+    p = S.apply(S.record(E, tile_k=32), E, pw)
+    assert (p["K"], p["k_tiles"], p["tail_k"]) == (36, 2, 4)
+    assert S.apply(S.record(E, tile_k=64), E, pw)["reason"] == S.R_FACTOR_GT_K
+    assert S.apply(S.record(E), E, cfg1_shape())["K"] == 64 * 3 * 3
 
 
-def test_ring_stages_apply_to_whole_item_operands_and_are_reformulated_elsewhere():
-    bf = S.DT_BF16
-    conv = S.conv_shape(32, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, bf)
-    rec = S.record(E, S.SK_MFMA, 64, 64, 64, 32, 32, 32, 1, 0, 8, 8, 4)
-    p = S.apply(rec, E, conv)
-    # four unpadded buffers of (64 + 64) rows x 64 bf16
-    assert (p["status"], p["stages"], p["lds_bytes"]) == (S.OK, 4, 4 * 128 * 64 * 2)
-    # a narrower vector knob gathers element by element: no ring, two padded stages
-    p = S.apply(dict(rec, vec=4), E, conv)
-    assert (p["stages"], p["lds_bytes"]) == (2, 2 * 128 * (64 + 8) * 2)
-    # 3 input channels never fill an item
-    stem = S.conv_shape(32, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3, bf)
-    assert S.apply(rec, E, stem)["stages"] == 2
-    # the [K][N] operand of a non-transposed batch matmul stays on the register pipeline
-    bm = S.CLS_BATCH_MATMUL
-    r7 = dict(rec, cls=bm, stages=3)
-    assert S.apply(r7, bm, S.gemm_shape(4, 128, 128, 64, 0, bf))["stages"] == 2
-    assert S.apply(r7, bm, S.gemm_shape(4, 128, 128, 64, 1, bf))["stages"] == 3
-    # 64 threads cannot cover whole 16-row groups of 8-chunk rows: (64 / 16) % 8 != 0
-    one_wave = S.record(E, S.SK_MFMA, 32, 32, 64, 32, 32, 32, 1, 0, 8, 8, 3)
-    assert S.apply(one_wave, E, conv)["stages"] == 2
-    # five stages is not a record
-    assert S.apply(dict(rec, stages=5), E, conv)["status"] == S.ERR_BAD_ARG
-    # the ring can exceed the LDS budget where two stages fit
-    big = S.record(E, S.SK_MFMA, 256, 128, 64, 64, 64, 32, 1, 0, 8, 8, 4)
-    wide = S.conv_shape(32, 64, 56, 56, 256, 3, 3, 1, 1, 1, 1, bf)
-    assert S.apply(big, E, wide)["reason"] == S.R_LDS and S.apply(dict(big, stages=3), E, wide)["status"] == S.OK
+def test_depthwise_vector_width_is_reformulated_to_the_channel_count():
+    """Section 4.1: a knob is reformulated where it can be; the vector width of the depthwise sketch
+    becomes the widest power of two that divides the channel count, and the workgroup's lanes then
+    cover tile_k times as many planes."""
+    dw = S.CLS_DWCONV_BIAS_RELU6
+    def plan(c, vec, tile_k=16, n=2):
+        rec = S.record(dw, S.SK_DWCONV, 4, 4, tile_k, 1, 1, 0, 1, 0, vec, 1, 1)
+        return S.apply(rec, dw, S.conv_shape(n, c, 14, 14, c, 3, 3, 1, 1, 1, 1))
+    assert plan(96, 4)["tile_k"] == 64 and plan(96, 2)["tile_k"] == 32 and plan(96, 1)["tile_k"] == 16
+    assert plan(36, 8)["tile_k"] == 64       # fp32: at most four elements per access
+    assert plan(18, 4)["tile_k"] == 32 and plan(27, 4)["tile_k"] == 16
+    p = plan(96, 4)
+    assert (p["K"], p["k_tiles"], p["block"], p["grid"]) == (192, 3, 16 * 16, 4 * 4 * 3)
+    assert plan(8, 4, tile_k=16, n=1)["reason"] == S.R_FACTOR_GT_K   # 64 planes asked of 8
 
 
 def test_malformed_records_and_shapes_are_argument_errors():
