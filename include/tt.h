@@ -196,7 +196,8 @@ enum { TT_STRICT_DIVISIBLE = 1 }; /* flags of tt_schedule_apply: factors must di
 /* Library version and a human-readable name for a status code (static storage). */
 int tt_version(void);
 const char *tt_status_name(int status);
-/* Text of the last failed HIP call on this thread (what, HIP's message, HIP's code); "" if none. */
+/* Text of the last failed HIP call on this thread (what, HIP's message, HIP's code), or of the last
+ * refusal of tt_conv2d_bias_relu_noalloc for lack of static workspace; "" if none. */
 const char *tt_last_error(void);
 
 /*
@@ -246,6 +247,21 @@ int64_t tt_debug_fast_div(uint32_t n, uint32_t d);
 int tt_conv2d_bias_relu(const void *x, const void *w, const void *bias, const void *residual, void *y,
                         const tt_conv_shape *shape, int cls, const tt_schedule *sched, void *ws,
                         size_t ws_bytes, void *stream);
+
+/*
+ * The same operator for callers that cannot allocate device memory and hold no workspace of their own:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Split-K
+ * partial sums go to an array of TT_STATIC_WORKSPACE_BYTES that is part of the library's device code
+ * (one copy per GPU, held until the process ends); the call allocates and frees nothing.  A (schedule,
+ * shape) whose tt_plan.workspace_bytes exceeds that size is refused with TT_ERR_WORKSPACE (tt_last_error
+ * says so) and nothing is launched.  Results are those of tt_conv2d_bias_relu, bit for bit.  Every call
+ * on a GPU uses that GPU's one array: calls that may overlap on one GPU (different streams, different
+ * host threads) race on it and must be serialised by the caller; calls on one stream are ordered.
+ * Nothing in the array has to be cleared between calls: every partial sum a call reads it has written.
+ */
+#define TT_STATIC_WORKSPACE_BYTES (16 * 1024 * 1024)
+int tt_conv2d_bias_relu_noalloc(const void *x, const void *w, const void *bias, const void *residual, void *y,
+                                const tt_conv_shape *shape, int cls, const tt_schedule *sched, void *stream);
 
 /*
  * dense (+bias) (+activation): y[m,o] = act(bias[o] + sum_i x[m,i] w[o,i]) (Table 1 class D;

@@ -93,7 +93,7 @@ class tt_sweep_row(Structure):
 
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
-           "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
+           "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_conv2d_bias_relu_noalloc", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
            "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_num_variants", "tt_select_donor")
 
 
@@ -115,6 +115,8 @@ def _load():
     lib.tt_debug_tile_map.argtypes = [POINTER(tt_plan), c_void_p, c_void_p]
     lib.tt_conv2d_bias_relu.argtypes = [c_void_p] * 5 + [POINTER(tt_conv_shape), ctypes.c_int, POINTER(tt_schedule),
                                                          c_void_p, c_size_t, c_void_p]
+    lib.tt_conv2d_bias_relu_noalloc.argtypes = [c_void_p] * 5 + [POINTER(tt_conv_shape), ctypes.c_int,
+                                                                 POINTER(tt_schedule), c_void_p]
     lib.tt_dense_bias_relu.argtypes = [c_void_p] * 4 + [POINTER(tt_gemm_shape), ctypes.c_int, POINTER(tt_schedule),
                                                         c_void_p, c_size_t, c_void_p]
     lib.tt_batch_matmul.argtypes = [c_void_p] * 3 + [POINTER(tt_gemm_shape), POINTER(tt_schedule), c_void_p,
@@ -286,6 +288,17 @@ def tt_conv2d_bias_relu(x, w, bias, residual, shape, cls, sched=None, ws=None, y
                                  0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "tt_conv2d_bias_relu")
     return y
+
+
+TT_STATIC_WORKSPACE_BYTES = 16 * 1024 * 1024
+
+
+def tt_conv2d_bias_relu_noalloc(x, w, bias, residual, y, shape, cls, sched=None):
+    """The conv operator with the library's static split-K workspace; `y` is the caller's (nothing is allocated)."""
+    cs = to_c_shape(shape)
+    rc = lib.tt_conv2d_bias_relu_noalloc(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), byref(cs), cls,
+                                         byref(sched) if sched is not None else None, _stream())
+    return rc
 
 
 def tt_dense_bias_relu(x, w, bias, shape, cls, sched=None, ws=None, y=None):

@@ -5,6 +5,7 @@
 #include <chrono>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "tt_internal.h"
@@ -80,6 +81,51 @@ int run_contraction(ContractArgs &g, const tt_plan &plan, int family, void *stre
 }
 
 } // namespace
+
+// ---- split-K partial sums without a caller's workspace ----------------------------------------------
+// One array per GPU, part of the library's code object: it exists from the moment the library is loaded
+// on a device until the process ends.  In host code the array's name is only a handle; the address the
+// kernels get comes from hipGetSymbolAddress, asked for once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[TT_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+
+int static_workspace(void **ptr)
+{
+    static std::mutex guard;
+    static void *per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return note_hip_error((int)e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return TT_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return note_hip_error((int)e, "hipGetSymbolAddress(scratch)");
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return TT_OK;
+}
+
+} // namespace
+
+extern "C" int tt_conv2d_bias_relu_noalloc(const void *x, const void *w, const void *bias, const void *residual,
+                                           void *y, const tt_conv_shape *shape, int cls, const tt_schedule *sched,
+                                           void *stream)
+{
+    void *ws = nullptr;
+    if (const int rc = static_workspace(&ws); rc != TT_OK) return rc;
+    const int rc = tt_conv2d_bias_relu(x, w, bias, residual, y, shape, cls, sched, ws, TT_STATIC_WORKSPACE_BYTES, stream);
+    if (rc == TT_ERR_WORKSPACE)
+        snprintf(tt::g_last_error, sizeof tt::g_last_error,
+                 "tt_conv2d_bias_relu_noalloc: the split-K partial sums of this (schedule, shape) exceed the "
+                 "library's static workspace of %d bytes", (int)TT_STATIC_WORKSPACE_BYTES);
+    return rc;
+}
 
 extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bias, const void *residual, void *y,
                                    const tt_conv_shape *shape, int cls, const tt_schedule *sched, void *ws,
