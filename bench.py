@@ -74,13 +74,9 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
     n_invalid = sum(r["n_invalid"] for r in rows)
     out["transfer_invalid_pairs"] = n_invalid
     log(f"[sweep] {evals} pairs in {wall:.1f}s, {n_invalid} invalid")
-    spaces = {}
     t0 = time.time()
     for k, dk, r in zip(targets, dks, rows):
-        key = (k.cls, k.shape.dtype)
-        if key not in spaces:
-            spaces[key] = api.tt_schedule_space(k.cls, k.shape.dtype, args.level)
-        best, best_us, default_us, n_valid, n_rec = tune.native_sweep(dk, args.level, space=spaces[key])
+        best, best_us, default_us, n_valid, n_rec = tune.native_sweep(dk, args.level)
         chosen = pool[r["chosen"]] if r["chosen"] >= 0 else None
         out["kernels"].append(dict(
             name=k.name, cls=k.cls, chosen_pool_index=r["chosen"],

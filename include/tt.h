@@ -298,13 +298,19 @@ typedef struct tt_sweep_opts {
     int32_t max_launches;         /* cap on launches per sample (default 64)                            */
     int32_t flags;                /* TT_STRICT_DIVISIBLE                                                */
     int32_t allow_slower_than_default; /* 1: keep the best donor even if the default is faster         */
+    /* Cheaper sweeps over a large pool (Section 5.5: "sampling a subset of schedules"; Section 4.4.2:
+     * "prioritize kernel classes by the potential improvement"); see tt_sweep_plan for the rule. */
+    int32_t pair_budget;          /* 0: every same-class pair; > 0: at most this many donor evaluations */
+    int32_t prioritise;           /* 1: spend the budget on the kernels with the largest share of the
+                                     untuned time first; 0: sample the pairs uniformly                  */
+    uint64_t seed;                /* seed of the sampling                                               */
 } tt_sweep_opts;
 
 typedef struct tt_sweep_row {
     int32_t kernel;
     int32_t chosen;      /* index into the pool, -1 = the default schedule */
     int32_t n_valid, n_invalid, n_other_class;
-    int32_t reserved;
+    int32_t n_not_tried; /* same-class pairs a pair budget left out */
     double best_us, default_us;
 } tt_sweep_row;
 
@@ -313,15 +319,64 @@ typedef struct tt_sweep_row {
  * time the default schedule, then every pool record of the kernel's class;
  * records that do not apply are recorded as -1 and skipped; the fastest wins,
  * the default is the fallback and wins ties, equal donors go to the lowest
- * index.  rows (host, nk).  pair_us (host, nk * np doubles, may be NULL):
- * median microseconds per launch, -1 for an invalid pair, -2 for a record of
- * another class.  evaluations (host, may be NULL): number of timed pairs,
+ * index.  With opts->pair_budget > 0 every default is timed first and only the pairs
+ * tt_sweep_plan selects (weights = default time x use count) are tried.  rows (host, nk).  pair_us
+ * (host, nk * np doubles, may be NULL): median microseconds per launch, -1 for an invalid pair, -2 for
+ * a record of another class, -3 for a pair the budget left out.  evaluations (host, may be NULL): number of timed pairs,
  * sum_k (1 + same-class records).  wall_seconds (host, may be NULL): wall-clock of
  * the call, the paper's "search time".  Synchronises `stream`.
  */
 int tt_transfer_sweep(const tt_kernel_desc *kernels, int nk, const tt_schedule *pool, int np,
                       const tt_sweep_opts *opts, void *stream, tt_sweep_row *rows, double *pair_us,
                       int64_t *evaluations, double *wall_seconds);
+
+/*
+ * Which (kernel, donor) pairs a budgeted sweep evaluates; host only, a pure function of its arguments.
+ * The paper leaves the sampling open ("randomly or using some other selection heuristic", Section 5.5);
+ * this library's rule: every same-class pair (k, p) gets the 64-bit key splitmix64(seed + k * np + p + 1)
+ * (Steele, Lea and Flood's SplitMix64 finaliser applied to that counter).
+ *   prioritise = 0: the `pair_budget` pairs with the smallest keys are evaluated (ties: lower k * np + p),
+ *                   a uniform sample without replacement;
+ *   prioritise = 1: kernels are visited by decreasing weight[k] (its untuned time times its use count;
+ *                   ties: lower k); each takes all its same-class pairs while the budget lasts, the
+ *                   kernel the budget runs out on takes its pairs with the smallest keys.
+ * pair_budget <= 0 or not below the number of same-class pairs selects them all.  mask (nk * np bytes):
+ * 1 = evaluate.  *selected (may be NULL) receives the count.  weight may be NULL when prioritise = 0.
+ */
+int tt_sweep_plan(const int32_t *kernel_cls, const double *weight, int nk, const int32_t *pool_cls, int np,
+                  int pair_budget, int prioritise, uint64_t seed, uint8_t *mask, int64_t *selected);
+
+/*
+ * The neighbourhood of a record for local refinement of a transferred schedule (the paper's outlook,
+ * Section 6: "vary parameters from schedules transfer-tuned from another model"): every well-formed
+ * record that differs from `base` in exactly one knob by one step: a tile, wave or K factor doubled or
+ * halved, the other matrix-core block, the neighbouring entries of the split list {1, 2, 3, 4, 6, 8, 12,
+ * 16, 32}, any other workgroup order, one stage more or fewer, unrolling on or off (8 / 1), the vector
+ * width doubled or halved.  Writes up to cap records to out (host), returns the count (cap = 0 to size).
+ * Only TT_SK_MFMA and TT_SK_DWCONV records have neighbours.
+ */
+int tt_refine_space(const tt_schedule *base, tt_schedule *out, int cap);
+
+/*
+ * Local refinement: time `base` and its neighbourhood on the kernel (standalone protocol of `opts`), move
+ * to the fastest, repeat up to `rounds` times or until no neighbour is faster.  best / best_us: the
+ * record reached and its time; base_us: the time of `base`; tried: number of timed pairs.  A base that
+ * does not apply to the kernel is the apply status and nothing is launched.  Synchronises `stream`.
+ */
+int tt_refine(const tt_kernel_desc *kernel, const tt_schedule *base, int rounds, const tt_sweep_opts *opts,
+              void *stream, tt_schedule *best, double *best_us, double *base_us, int32_t *tried);
+
+/*
+ * The exhaustive native sweep of ONE kernel (the stand-in for full auto-scheduling, Sections 3 and
+ * 5.2): walk tt_schedule_space(cls, dtype, level) with the `explore` protocol, re-try the `finalists`
+ * fastest records under every workgroup order and both unroll settings, then time the `finalists`
+ * fastest of those and the default with the `full` protocol.  best: the winner (the default record if
+ * nothing beats it); n_valid / n_records: records that applied / size of the space.  NULL option
+ * pointers select 1 / 3 / 60 us / 16 for explore and the defaults of tt_sweep_opts for full.
+ */
+int tt_native_sweep(const tt_kernel_desc *kernel, int level, int finalists, const tt_sweep_opts *explore,
+                    const tt_sweep_opts *full, void *stream, tt_schedule *best, double *best_us,
+                    double *default_us, int32_t *n_valid, int32_t *n_records);
 
 /*
  * Time ONE (kernel, schedule) pair standalone with the sweep's protocol (warm-up,

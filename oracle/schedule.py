@@ -29,6 +29,14 @@ What the paper fixes (Sections 4.1-4.3) and what is written out here:
   known: every kernel is tried with the default schedule and with every donor
   record of its class, invalid pairs are marked -1 and skipped, the fastest is
   kept, the default is the fallback.
+* ``sweep_plan``: which pairs a sweep with a pair budget evaluates.  The paper
+  only names the idea (Section 5.5: sample a subset of the schedules, "randomly
+  or using some other selection heuristic"; Section 4.4.2: prioritise kernel
+  classes by their potential); the rule written out here is this repository's
+  reading: SplitMix64 keys per pair, the smallest keys are kept; with
+  prioritisation kernels are served in order of their share of untuned time.
+* ``refine_neighbours``: the one-knob neighbourhood of a record, for the local
+  refinement the paper proposes as future work (Section 6).
 
 Readings of points the paper leaves open are listed in the repository's design
 notes; the ones that matter here: factors are compared against the fused GEMM
@@ -421,6 +429,8 @@ def default_schedule(cls: int, shape: dict) -> dict:
 
 
 # ---- the sweep once times are known (paper Section 4.3) ------------------------------------------
+NOT_TRIED = -3.0
+
 def evaluation_count(kernel_classes, pool_classes) -> int:
     """Pairs a sweep evaluates: every kernel once with the default plus once per same-class donor."""
     return sum(1 + sum(1 for pc in pool_classes if pc == kc) for kc in kernel_classes)
@@ -443,6 +453,8 @@ def select(kernel_classes, pool_classes, pair_us, default_us, allow_slower_than_
             if pc != kc:
                 continue
             t = pair_us[k][p]
+            if t == NOT_TRIED:      # left out by a pair budget: neither valid nor invalid
+                continue
             if t < 0:
                 n_invalid += 1
                 continue
@@ -458,3 +470,82 @@ def select(kernel_classes, pool_classes, pair_us, default_us, allow_slower_than_
 def model_selection_score(target_class_cost: dict, candidate_class_count: dict) -> float:
     """Paper Eq. 1: sum over the target's classes of P_c^2 * sqrt(|W_Tc|)."""
     return sum(p * p * (candidate_class_count.get(c, 0) ** 0.5) for c, p in target_class_cost.items())
+
+
+# ---- cheaper sweeps (paper Sections 5.5 and 4.4.2: ideas only; the rule is this repository's) -----
+MASK64 = (1 << 64) - 1
+
+
+def splitmix64(x: int) -> int:
+    """Output function of SplitMix64 (Steele, Lea, Flood 2014) applied to the counter x."""
+    x = (x + 0x9E3779B97F4A7C15) & MASK64
+    x = ((x ^ (x >> 30)) * 0xBF58476D1CE4E5B9) & MASK64
+    x = ((x ^ (x >> 27)) * 0x94D049BB133111EB) & MASK64
+    return x ^ (x >> 31)
+
+
+def sweep_plan(kernel_classes, weights, pool_classes, pair_budget, prioritise=False, seed=0):
+    """mask[k][p] = 1 for the (kernel, donor) pairs a budgeted sweep evaluates.
+
+    Every same-class pair gets the key splitmix64(seed + k * np + p + 1).  Without
+    prioritisation the ``pair_budget`` smallest keys are taken (a uniform sample
+    without replacement).  With it, kernels are served by decreasing weight (their
+    untuned time times their use count; ties: lower index), each taking all its pairs
+    while the budget lasts; the kernel the budget runs out on keeps its smallest keys.
+    """
+    nk, np_ = len(kernel_classes), len(pool_classes)
+    pairs = {k: [] for k in range(nk)}
+    for k in range(nk):
+        for p in range(np_):
+            if pool_classes[p] == kernel_classes[k]:
+                i = k * np_ + p
+                pairs[k].append((splitmix64((seed + i + 1) & MASK64), i))
+    total = sum(len(v) for v in pairs.values())
+    mask = [[0] * np_ for _ in range(nk)]
+    if pair_budget <= 0 or pair_budget >= total:
+        chosen = [i for v in pairs.values() for _, i in v]
+    elif not prioritise:
+        chosen = [i for _, i in sorted(q for v in pairs.values() for q in v)[:pair_budget]]
+    else:
+        chosen, left = [], pair_budget
+        for k in sorted(range(nk), key=lambda k: (-weights[k], k)):
+            take = sorted(pairs[k])[:left] if len(pairs[k]) > left else pairs[k]
+            chosen += [i for _, i in take]
+            left -= len(take)
+            if left <= 0:
+                break
+    for i in chosen:
+        mask[i // np_][i % np_] = 1
+    return mask
+
+
+SPLIT_STEPS = (1, 2, 3, 4, 6, 8, 12, 16, 32)
+
+
+def refine_neighbours(rec: dict):
+    """Well-formed records that differ from ``rec`` in exactly one knob by one step (Section 6's outlook)."""
+    out = []
+
+    def consider(**change):
+        r = dict(rec, **change)
+        if r != rec and record_is_well_formed(r) and r not in out:
+            out.append(r)
+
+    if rec["sketch"] in (SK_MFMA, SK_DWCONV):
+        for f in ("tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "vec"):
+            if rec[f] % 2 == 0:
+                consider(**{f: rec[f] // 2})
+            consider(**{f: rec[f] * 2})
+        for order in range(6):
+            consider(order=order)
+        consider(stages=rec["stages"] - 1)
+        consider(stages=rec["stages"] + 1)
+        consider(unroll=1 if rec["unroll"] >= 2 else 8)
+    if rec["sketch"] == SK_MFMA:
+        consider(mfma=32 if rec["mfma"] == 16 else 16)
+        if rec["split_k"] in SPLIT_STEPS:
+            at = SPLIT_STEPS.index(rec["split_k"])
+            for j in (at - 1, at + 1):
+                if 0 <= j < len(SPLIT_STEPS):
+                    consider(split_k=SPLIT_STEPS[j])
+    return out

@@ -84,17 +84,18 @@ class tt_kernel_desc(Structure):
 
 class tt_sweep_opts(Structure):
     _fields_ = [(n, c_int32) for n in ("warmup", "samples", "min_sample_us", "max_launches", "flags",
-                                       "allow_slower_than_default")]
+                                       "allow_slower_than_default", "pair_budget", "prioritise")]
+    _fields_ += [("seed", ctypes.c_uint64)]
 
 
 class tt_sweep_row(Structure):
-    _fields_ = [(n, c_int32) for n in ("kernel", "chosen", "n_valid", "n_invalid", "n_other_class", "reserved")]
+    _fields_ = [(n, c_int32) for n in ("kernel", "chosen", "n_valid", "n_invalid", "n_other_class", "n_not_tried")]
     _fields_ += [("best_us", c_double), ("default_us", c_double)]
 
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
            "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_conv2d_bias_relu_noalloc", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
-           "tt_transfer_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_num_variants", "tt_select_donor")
+           "tt_transfer_sweep", "tt_sweep_plan", "tt_refine_space", "tt_refine", "tt_native_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_num_variants", "tt_select_donor")
 
 
 def _load():
@@ -125,6 +126,14 @@ def _load():
     lib.tt_transfer_sweep.argtypes = [POINTER(tt_kernel_desc), ctypes.c_int, POINTER(tt_schedule), ctypes.c_int,
                                       POINTER(tt_sweep_opts), c_void_p, POINTER(tt_sweep_row), POINTER(c_double),
                                       POINTER(c_int64), POINTER(c_double)]
+    lib.tt_sweep_plan.argtypes = [POINTER(c_int32), POINTER(c_double), ctypes.c_int, POINTER(c_int32), ctypes.c_int,
+                                  ctypes.c_int, ctypes.c_int, ctypes.c_uint64, POINTER(ctypes.c_uint8), POINTER(c_int64)]
+    lib.tt_refine_space.argtypes = [POINTER(tt_schedule), POINTER(tt_schedule), ctypes.c_int]
+    lib.tt_refine.argtypes = [POINTER(tt_kernel_desc), POINTER(tt_schedule), ctypes.c_int, POINTER(tt_sweep_opts), c_void_p,
+                              POINTER(tt_schedule), POINTER(c_double), POINTER(c_double), POINTER(c_int32)]
+    lib.tt_native_sweep.argtypes = [POINTER(tt_kernel_desc), ctypes.c_int, ctypes.c_int, POINTER(tt_sweep_opts),
+                                    POINTER(tt_sweep_opts), c_void_p, POINTER(tt_schedule), POINTER(c_double),
+                                    POINTER(c_double), POINTER(c_int32), POINTER(c_int32)]
     lib.tt_time_pair.argtypes = [POINTER(tt_kernel_desc), POINTER(tt_schedule), POINTER(tt_sweep_opts), c_void_p,
                                  POINTER(c_double), POINTER(c_double)]
     lib.tt_run_kernels.argtypes = [POINTER(tt_kernel_desc), POINTER(POINTER(tt_schedule)), ctypes.c_int, ctypes.c_int,
@@ -391,8 +400,51 @@ class DeviceKernel:
         return rc
 
 
-def make_opts(warmup=3, samples=10, min_sample_us=200, max_launches=64, flags=0, allow_slower_than_default=0):
-    return tt_sweep_opts(warmup, samples, min_sample_us, max_launches, flags, allow_slower_than_default)
+def make_opts(warmup=3, samples=10, min_sample_us=200, max_launches=64, flags=0, allow_slower_than_default=0,
+              pair_budget=0, prioritise=0, seed=0):
+    return tt_sweep_opts(warmup, samples, min_sample_us, max_launches, flags, allow_slower_than_default, pair_budget,
+                         prioritise, seed)
+
+
+def tt_sweep_plan(kernel_cls, weight, pool_cls, pair_budget, prioritise=0, seed=0):
+    """mask[k][p] (1 = evaluate) of a budgeted sweep; host only."""
+    nk, np_ = len(kernel_cls), len(pool_cls)
+    kc = (c_int32 * max(nk, 1))(*kernel_cls)
+    pc = (c_int32 * max(np_, 1))(*pool_cls)
+    w = (c_double * max(nk, 1))(*[float(v) for v in weight]) if weight is not None else None
+    mask = (ctypes.c_uint8 * max(nk * np_, 1))()
+    sel = c_int64(0)
+    _check(lib.tt_sweep_plan(kc, w, nk, pc, np_, pair_budget, prioritise, seed, mask, byref(sel)), "tt_sweep_plan")
+    return [[int(mask[k * np_ + p]) for p in range(np_)] for k in range(nk)], int(sel.value)
+
+
+def tt_refine_space(base: tt_schedule):
+    n = lib.tt_refine_space(byref(base), None, 0)
+    if n < 0:
+        raise TTError(n, "tt_refine_space")
+    arr = (tt_schedule * max(n, 1))()
+    lib.tt_refine_space(byref(base), arr, n)
+    return [arr[i].copy() for i in range(n)]
+
+
+def tt_refine(kernel, base: tt_schedule, rounds=2, opts=None):
+    """(status, best record, best_us, base_us, pairs timed): local refinement of a record on a kernel."""
+    best = tt_schedule()
+    bu, su, tried = c_double(-1.0), c_double(-1.0), c_int32(0)
+    rc = lib.tt_refine(byref(kernel.desc), byref(base), rounds, byref(opts) if opts is not None else None, _stream(),
+                       byref(best), byref(bu), byref(su), byref(tried))
+    return rc, best, bu.value, su.value, tried.value
+
+
+def tt_native_sweep(kernel, level=1, finalists=4, explore=None, full=None):
+    """(best record, best_us, default_us, n_valid, n_records): the exhaustive sweep of one kernel."""
+    best = tt_schedule()
+    bu, du, nv, nr = c_double(-1.0), c_double(-1.0), c_int32(0), c_int32(0)
+    rc = lib.tt_native_sweep(byref(kernel.desc), level, finalists, byref(explore) if explore is not None else None,
+                             byref(full) if full is not None else None, _stream(), byref(best), byref(bu), byref(du),
+                             byref(nv), byref(nr))
+    _check(rc, "tt_native_sweep")
+    return best, bu.value, du.value, nv.value, nr.value
 
 
 def tt_time_pair(kernel: DeviceKernel, sched=None, opts=None):
@@ -420,7 +472,8 @@ def tt_transfer_sweep(kernels, pool, opts=None):
     _check(rc, "tt_transfer_sweep")
     table = [[pair[k * np_ + p] for p in range(np_)] for k in range(nk)]
     out_rows = [dict(kernel=rows[i].kernel, chosen=rows[i].chosen, n_valid=rows[i].n_valid,
-                     n_invalid=rows[i].n_invalid, n_other_class=rows[i].n_other_class, best_us=rows[i].best_us,
+                     n_invalid=rows[i].n_invalid, n_other_class=rows[i].n_other_class,
+                     n_not_tried=rows[i].n_not_tried, best_us=rows[i].best_us,
                      default_us=rows[i].default_us) for i in range(nk)]
     return out_rows, table, evals.value, wall.value
 

@@ -301,7 +301,13 @@ tt_sweep_opts resolve(const tt_sweep_opts *o)
     r.max_launches = 64;
     r.flags = 0;
     r.allow_slower_than_default = 0;
+    r.pair_budget = 0;
+    r.prioritise = 0;
+    r.seed = 0;
     if (o) {
+        r.pair_budget = o->pair_budget;
+        r.prioritise = o->prioritise;
+        r.seed = o->seed;
         if (o->warmup >= 0) r.warmup = o->warmup;
         if (o->samples > 0) r.samples = o->samples;
         if (o->min_sample_us > 0) r.min_sample_us = o->min_sample_us;
@@ -395,27 +401,39 @@ extern "C" int tt_transfer_sweep(const tt_kernel_desc *kernels, int nk, const tt
     hipStream_t s = static_cast<hipStream_t>(stream);
     Timer timer;
     if (!timer.ok) return TT_ERR_HIP;
-    std::vector<double> local((size_t)nk * np, -2.0), defaults(nk, 0.0);
+    std::vector<double> local((size_t)nk * np, -2.0), defaults(nk, 0.0), weight(nk, 0.0);
     std::vector<int32_t> kcls(nk), pcls(np);
     for (int p = 0; p < np; ++p) pcls[p] = pool[p].cls;
     int64_t evals = 0;
+    // the default ("untuned") schedule is always evaluated: it is the baseline and the fallback
     for (int k = 0; k < nk; ++k) {
         if (!kernels[k].shape) return TT_ERR_BAD_ARG;
         kcls[k] = kernels[k].cls;
-        // the default ("untuned") schedule is always evaluated: it is the baseline and the fallback
-        int rc = time_pair(kernels[k], nullptr, o, s, timer, &defaults[k], nullptr);
+        const int rc = time_pair(kernels[k], nullptr, o, s, timer, &defaults[k], nullptr);
         if (rc != TT_OK) return rc;
+        weight[k] = defaults[k] * std::max(1, kernels[k].use_count);
         ++evals;
+    }
+    // which same-class pairs are tried: all of them, or the budgeted subset
+    std::vector<uint8_t> mask((size_t)nk * np + 1, 0);
+    if (const int rc = tt_sweep_plan(kcls.data(), weight.data(), nk, pcls.data(), np, o.pair_budget, o.prioritise, o.seed,
+                                     mask.data(), nullptr);
+        rc != TT_OK)
+        return rc;
+    for (int k = 0; k < nk; ++k)
         for (int p = 0; p < np; ++p) {
             if (pool[p].cls != kernels[k].cls) continue; // other classes are never tried (Section 4.2)
+            if (!mask[(size_t)k * np + p]) {
+                local[(size_t)k * np + p] = -3.0;
+                continue;
+            }
             ++evals;
             double us = -1.0;
-            rc = time_pair(kernels[k], &pool[p], o, s, timer, &us, nullptr);
+            const int rc = time_pair(kernels[k], &pool[p], o, s, timer, &us, nullptr);
             if (rc == TT_ERR_HIP) return rc;
             // every other failure means "this record does not fit this kernel": the paper's -1
             local[(size_t)k * np + p] = rc == TT_OK ? us : -1.0;
         }
-    }
     if (hipStreamSynchronize(s) != hipSuccess) return TT_ERR_HIP;
     const int rc = tt_sweep_select(kcls.data(), nk, pcls.data(), np, local.data(), defaults.data(),
                                    o.allow_slower_than_default, rows);
@@ -423,5 +441,142 @@ extern "C" int tt_transfer_sweep(const tt_kernel_desc *kernels, int nk, const tt
     if (pair_us) std::copy(local.begin(), local.end(), pair_us);
     if (evaluations) *evaluations = evals;
     if (wall_seconds) *wall_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return TT_OK;
+}
+
+// ---- local refinement of a record (Section 6's outlook) and the native sweep of one kernel -----------------
+
+extern "C" int tt_refine(const tt_kernel_desc *kernel, const tt_schedule *base, int rounds, const tt_sweep_opts *opts,
+                         void *stream, tt_schedule *best, double *best_us, double *base_us, int32_t *tried)
+{
+    if (!kernel || !kernel->shape || !base || !best || rounds < 0) return TT_ERR_BAD_ARG;
+    const tt_sweep_opts o = resolve(opts);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timer timer;
+    if (!timer.ok) return TT_ERR_HIP;
+    double cur_us = 0.0;
+    int rc = time_pair(*kernel, base, o, s, timer, &cur_us, nullptr);
+    if (rc != TT_OK) return rc;
+    int32_t n = 1;
+    tt_schedule cur = *base;
+    if (base_us) *base_us = cur_us;
+    for (int r = 0; r < rounds; ++r) {
+        const int count = tt_refine_space(&cur, nullptr, 0);
+        if (count <= 0) break;
+        std::vector<tt_schedule> near(count);
+        tt_refine_space(&cur, near.data(), count);
+        int win = -1;
+        double win_us = cur_us;
+        for (int i = 0; i < count; ++i) {
+            double us = 0.0;
+            rc = time_pair(*kernel, &near[i], o, s, timer, &us, nullptr);
+            if (rc == TT_ERR_HIP) return rc;
+            if (rc != TT_OK) continue; // does not apply to this kernel, or no kernel implements it
+            ++n;
+            if (us < win_us) { // strict: the current record, then the lowest index, win ties
+                win_us = us;
+                win = i;
+            }
+        }
+        if (win < 0) break;
+        const int32_t keep_id = cur.id;
+        cur = near[win];
+        cur.id = keep_id;
+        cur_us = win_us;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) return TT_ERR_HIP;
+    *best = cur;
+    if (best_us) *best_us = cur_us;
+    if (tried) *tried = n;
+    return TT_OK;
+}
+
+extern "C" int tt_native_sweep(const tt_kernel_desc *kernel, int level, int finalists, const tt_sweep_opts *explore,
+                               const tt_sweep_opts *full, void *stream, tt_schedule *best, double *best_us,
+                               double *default_us, int32_t *n_valid, int32_t *n_records)
+{
+    if (!kernel || !kernel->shape || !best || finalists < 1) return TT_ERR_BAD_ARG;
+    tt_sweep_opts quick;
+    std::memset(&quick, 0, sizeof quick);
+    quick.warmup = 1;
+    quick.samples = 3;
+    quick.min_sample_us = 60;
+    quick.max_launches = 16;
+    const tt_sweep_opts ex = explore ? resolve(explore) : quick, fu = resolve(full);
+    const bool conv = is_conv_class(kernel->cls) || kernel->cls == TT_DWCONV_BIAS_RELU6;
+    const int dtype = conv ? static_cast<const tt_conv_shape *>(kernel->shape)->dtype
+                           : static_cast<const tt_gemm_shape *>(kernel->shape)->dtype;
+    const int count = tt_schedule_space(kernel->cls, dtype, level, nullptr, 0);
+    if (count < 0) return count;
+    std::vector<tt_schedule> space(std::max(count, 1));
+    tt_schedule_space(kernel->cls, dtype, level, space.data(), count);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timer timer;
+    if (!timer.ok) return TT_ERR_HIP;
+
+    // the `keep` fastest records of a list under one protocol, fastest first (ties: list order)
+    struct Timed {
+        double us;
+        int index;
+    };
+    int valid = 0;
+    const auto fastest = [&](const std::vector<tt_schedule> &list, int n, const tt_sweep_opts &o, size_t keep, bool count_valid,
+                             std::vector<tt_schedule> *out, std::vector<double> *out_us) -> int {
+        std::vector<Timed> t;
+        for (int i = 0; i < n; ++i) {
+            double us = 0.0;
+            const int rc = time_pair(*kernel, &list[i], o, s, timer, &us, nullptr);
+            if (rc == TT_ERR_HIP) return rc;
+            if (rc != TT_OK) continue;
+            if (count_valid) ++valid;
+            t.push_back({us, i});
+        }
+        std::stable_sort(t.begin(), t.end(), [](const Timed &a, const Timed &b) { return a.us < b.us; });
+        out->clear();
+        if (out_us) out_us->clear();
+        for (size_t i = 0; i < t.size() && i < keep; ++i) {
+            out->push_back(list[t[i].index]);
+            if (out_us) out_us->push_back(t[i].us);
+        }
+        return TT_OK;
+    };
+    std::vector<tt_schedule> top;
+    int rc = fastest(space, count, ex, (size_t)finalists, true, &top, nullptr);
+    if (rc != TT_OK) return rc;
+    if (!top.empty() && top[0].sketch == TT_SK_MFMA) {
+        // the enumerated space carries one unroll setting and (below level 2) two workgroup orders: the
+        // finalists are re-tried under all of them
+        std::vector<tt_schedule> wide;
+        for (const tt_schedule &f : top)
+            for (int order = 0; order < 6; ++order)
+                for (int unroll : {8, 1}) {
+                    tt_schedule r = f;
+                    r.order = order;
+                    r.unroll = unroll;
+                    bool seen = false;
+                    for (const tt_schedule &w : wide) seen = seen || std::memcmp(&w, &r, sizeof(int32_t) * 13) == 0;
+                    if (!seen) wide.push_back(r);
+                }
+        rc = fastest(wide, (int)wide.size(), ex, (size_t)finalists, false, &top, nullptr);
+        if (rc != TT_OK) return rc;
+    }
+    std::vector<double> top_us;
+    rc = fastest(top, (int)top.size(), fu, 1, false, &top, &top_us);
+    if (rc != TT_OK) return rc;
+    double def_us = 0.0;
+    rc = time_pair(*kernel, nullptr, fu, s, timer, &def_us, nullptr);
+    if (rc != TT_OK) return rc;
+    if (hipStreamSynchronize(s) != hipSuccess) return TT_ERR_HIP;
+    if (!top.empty() && top_us[0] < def_us) { // the default wins ties
+        *best = top[0];
+        if (best_us) *best_us = top_us[0];
+    } else {
+        rc = tt_schedule_default(kernel->cls, kernel->shape, best);
+        if (rc != TT_OK) return rc;
+        if (best_us) *best_us = def_us;
+    }
+    if (default_us) *default_us = def_us;
+    if (n_valid) *n_valid = valid;
+    if (n_records) *n_records = count;
     return TT_OK;
 }

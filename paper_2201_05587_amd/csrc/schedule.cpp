@@ -460,6 +460,10 @@ extern "C" int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t 
                 continue;
             }
             const double t = pair_us[(size_t)k * np + p];
+            if (t == -3.0) {
+                ++row.n_not_tried; // left out by the sweep's budget
+                continue;
+            }
             if (t < 0) {
                 ++row.n_invalid; // does not apply to this kernel: skipped
                 continue;
@@ -475,6 +479,120 @@ extern "C" int tt_sweep_select(const int32_t *kernel_cls, int nk, const int32_t 
         rows[k] = row;
     }
     return TT_OK;
+}
+
+// SplitMix64 (Steele, Lea, Flood: "Fast splittable pseudorandom number generators", 2014): the output
+// function applied to a counter; used as a counter-based generator of sampling keys.
+static uint64_t splitmix64(uint64_t x)
+{
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+
+extern "C" int tt_sweep_plan(const int32_t *kernel_cls, const double *weight, int nk, const int32_t *pool_cls, int np,
+                             int pair_budget, int prioritise, uint64_t seed, uint8_t *mask, int64_t *selected)
+{
+    if (nk < 0 || np < 0 || !mask || (nk && !kernel_cls) || (np && !pool_cls) || (prioritise && nk && !weight))
+        return TT_ERR_BAD_ARG;
+    struct Pair {
+        uint64_t key;
+        int64_t index;
+    };
+    std::vector<std::vector<Pair>> per_kernel(nk);
+    int64_t total = 0;
+    for (int k = 0; k < nk; ++k)
+        for (int p = 0; p < np; ++p) {
+            const int64_t i = (int64_t)k * np + p;
+            mask[i] = 0;
+            if (pool_cls[p] != kernel_cls[k]) continue;
+            per_kernel[k].push_back({splitmix64(seed + (uint64_t)i + 1), i});
+            ++total;
+        }
+    const auto by_key = [](const Pair &a, const Pair &b) { return a.key != b.key ? a.key < b.key : a.index < b.index; };
+    int64_t chosen = 0;
+    if (pair_budget <= 0 || pair_budget >= total) {
+        for (auto &v : per_kernel)
+            for (const Pair &q : v) mask[q.index] = 1;
+        chosen = total;
+    } else if (!prioritise) {
+        std::vector<Pair> all;
+        for (auto &v : per_kernel) all.insert(all.end(), v.begin(), v.end());
+        std::sort(all.begin(), all.end(), by_key);
+        for (int64_t i = 0; i < pair_budget; ++i) mask[all[i].index] = 1;
+        chosen = pair_budget;
+    } else {
+        std::vector<int> order(nk);
+        for (int k = 0; k < nk; ++k) order[k] = k;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return weight[a] > weight[b]; });
+        int64_t left = pair_budget;
+        for (int k : order) {
+            auto &v = per_kernel[k];
+            if (left <= 0) break;
+            if ((int64_t)v.size() > left) std::sort(v.begin(), v.end(), by_key);
+            const int64_t take = std::min<int64_t>(left, (int64_t)v.size());
+            for (int64_t i = 0; i < take; ++i) mask[v[i].index] = 1;
+            left -= take;
+            chosen += take;
+        }
+    }
+    if (selected) *selected = chosen;
+    return TT_OK;
+}
+
+extern "C" int tt_refine_space(const tt_schedule *base, tt_schedule *out, int cap)
+{
+    if (!base || cap < 0 || (cap && !out) || !record_well_formed(*base)) return TT_ERR_BAD_ARG;
+    std::vector<tt_schedule> recs;
+    const auto consider = [&](tt_schedule r) {
+        if (!record_well_formed(r)) return;
+        if (std::memcmp(&r, base, sizeof(int32_t) * 13) == 0) return; // the thirteen knobs lead the record
+        r.id = (int32_t)recs.size();
+        recs.push_back(r);
+    };
+    const tt_schedule &b = *base;
+    if (b.sketch == TT_SK_MFMA || b.sketch == TT_SK_DWCONV) {
+        int32_t tt_schedule::*factors[] = {&tt_schedule::tile_m, &tt_schedule::tile_n, &tt_schedule::tile_k,
+                                           &tt_schedule::wave_m, &tt_schedule::wave_n, &tt_schedule::vec};
+        for (auto f : factors)
+            for (int up = 0; up < 2; ++up) {
+                tt_schedule r = b;
+                r.*f = up ? b.*f * 2 : b.*f / 2;
+                if (r.*f >= 1 && (up || b.*f % 2 == 0)) consider(r);
+            }
+        for (int order = 0; order < 6; ++order) {
+            tt_schedule r = b;
+            r.order = order;
+            consider(r);
+        }
+        for (int d = -1; d <= 1; d += 2) {
+            tt_schedule r = b;
+            r.stages = b.stages + d;
+            consider(r);
+        }
+        tt_schedule u = b;
+        u.unroll = b.unroll >= 2 ? 1 : 8;
+        consider(u);
+    }
+    if (b.sketch == TT_SK_MFMA) {
+        tt_schedule r = b;
+        r.mfma = b.mfma == 16 ? 32 : 16;
+        consider(r);
+        static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 32};
+        int at = -1;
+        for (int i = 0; i < 9; ++i)
+            if (splits[i] == b.split_k) at = i;
+        if (at >= 0)
+            for (int d = -1; d <= 1; d += 2)
+                if (at + d >= 0 && at + d < 9) {
+                    tt_schedule q = b;
+                    q.split_k = splits[at + d];
+                    consider(q);
+                }
+    }
+    for (size_t i = 0; i < recs.size() && (int)i < cap; ++i) out[i] = recs[i];
+    return (int)recs.size();
 }
 
 extern "C" int tt_select_donor(const double *class_cost, int num_classes, const int32_t *donor_class_count,

@@ -26,57 +26,26 @@ def shape_ints(shape) -> List[int]:
     return vals + [0] * (12 - len(vals))
 
 
-def native_sweep(dk: api.DeviceKernel, level: int = 1, finalists: int = 4, space: Optional[list] = None):
-    """Exhaustive sweep of the class's schedule space on the kernel's own shape.
+def native_sweep(dk: api.DeviceKernel, level: int = 1, finalists: int = 4):
+    """Exhaustive sweep of the class's schedule space on the kernel's own shape (runs in the library).
 
-    Returns (best_record, best_us, default_us, n_valid, n_records).  The space is walked with the
-    cheap protocol; the `finalists` fastest records are then tried under every workgroup raster
-    order (the enumerated space of level 1 carries only the two plain ones; the XCD-contiguous
-    orders decide how often the L2 caches re-fetch shared operand tiles), and the fastest of those
-    and the default are re-timed with the full protocol.
+    Returns (best_record, best_us, default_us, n_valid, n_records); the record is None when nothing
+    beats the default schedule.
     """
-    dtype = dk.cshape.dtype
-    if space is None:
-        space = api.tt_schedule_space(dk.cls, dtype, level)
-    rows, table, _, _ = api.tt_transfer_sweep([dk], space, api.make_opts(**EXPLORE))
-    times = table[0]
-    ranked = sorted((t, i) for i, t in enumerate(times) if t >= 0)
-    top = [space[i] for _, i in ranked[:finalists]]
-    n_valid = len(ranked)
-    if not top:
-        rc, med, _ = api.tt_time_pair(dk, None, api.make_opts(**FULL))
-        return None, med, med, 0, len(space)
-    if top[0].sketch == api.TT_SK_MFMA:
-        seen, variants = set(), []
-        for rec in top:
-            for order in range(6):
-                r = rec.copy()
-                r.order = order
-                key = tuple(sorted(r.knobs().items()))
-                if key not in seen:
-                    seen.add(key)
-                    variants.append(r)
-        rows, table, _, _ = api.tt_transfer_sweep([dk], variants, api.make_opts(**EXPLORE))
-        ranked = sorted((t, i) for i, t in enumerate(table[0]) if t >= 0)
-        top = [variants[i] for _, i in ranked[:finalists]]
-    rows, table, _, _ = api.tt_transfer_sweep([dk], top, api.make_opts(**FULL))
-    r = rows[0]
-    best = top[r["chosen"]].copy() if r["chosen"] >= 0 else None
-    return best, r["best_us"], r["default_us"], n_valid, len(space)
+    best, best_us, default_us, n_valid, n_rec = api.tt_native_sweep(dk, level, finalists, api.make_opts(**EXPLORE),
+                                                                    api.make_opts(**FULL))
+    default = api.tt_schedule_default(dk.cls, dk.cshape)
+    return (None if best.knobs() == default.knobs() else best), best_us, default_us, n_valid, n_rec
 
 
 def tune_donors(kernels: Sequence[wl.Kernel], seed_cfg: int, level: int = 1, log=None) -> List[api.tt_schedule]:
     """Native-tune every donor kernel; each contributes its optimum as one pool record."""
     import torch
     pool: List[api.tt_schedule] = []
-    spaces: Dict[tuple, list] = {}
     for i, k in enumerate(kernels):
-        key = (k.cls, k.shape.dtype)
-        if key not in spaces:
-            spaces[key] = api.tt_schedule_space(k.cls, k.shape.dtype, level)
         dk = harness.device_kernel(k, wl.seed_for(seed_cfg, i), max_split=8)
         t0 = time.time()
-        best, best_us, default_us, n_valid, n_rec = native_sweep(dk, level, space=spaces[key])
+        best, best_us, default_us, n_valid, n_rec = native_sweep(dk, level)
         if best is None:
             best = api.tt_schedule_default(k.cls, k.shape)
         best.id = len(pool)

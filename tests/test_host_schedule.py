@@ -332,3 +332,55 @@ def test_choose_donor_pool_on_the_committed_sweep_outcomes():
             count[r.cls] = count.get(r.cls, 0) + 1
         want = S.model_selection_score({c: v / total for c, v in cost.items()}, count)
         assert abs(scores[n] - want) <= 1e-12 * max(1.0, want)
+
+
+def test_sweep_plan_matches_oracle():
+    rng = random.Random(11)
+    for it in range(300):
+        nk, np_ = rng.randrange(1, 7), rng.randrange(0, 12)
+        kc = [rng.randrange(3) for _ in range(nk)]
+        pc = [rng.randrange(3) for _ in range(np_)]
+        w = [rng.choice([1.0, 2.0, 2.0, 5.5, 9.0]) for _ in range(nk)]
+        total = S.evaluation_count(kc, pc) - nk
+        budget = rng.choice([0, 1, 2, 3, total - 1, total, total + 3, rng.randrange(0, total + 2)])
+        seed = rng.randrange(2 ** 64) if it % 3 else it
+        for prio in (0, 1):
+            want = S.sweep_plan(kc, w, pc, budget, bool(prio), seed)
+            got, selected = api.tt_sweep_plan(kc, w, pc, budget, prio, seed)
+            assert got == want, (kc, pc, w, budget, prio, seed)
+            assert selected == sum(map(sum, want))
+    assert api.tt_sweep_plan([1, 1], None, [1, 1, 1], 2, 0, 5)[1] == 2
+    with pytest.raises(api.TTError):
+        api.tt_sweep_plan([1], None, [1], 1, 1, 0)   # prioritising needs the weights
+
+
+def test_selection_with_untried_pairs_matches_oracle():
+    rng = random.Random(17)
+    for _ in range(100):
+        nk, np_ = rng.randrange(1, 5), rng.randrange(1, 7)
+        kc = [rng.randrange(2) for _ in range(nk)]
+        pc = [rng.randrange(2) for _ in range(np_)]
+        pair = [[rng.choice([-1.0, -3.0, 1.0, 2.0, 3.0]) for _ in range(np_)] for _ in range(nk)]
+        default = [rng.choice([1.5, 2.5]) for _ in range(nk)]
+        want = S.select(kc, pc, pair, default)
+        got = api.tt_sweep_select(kc, pc, pair, default)
+        assert [tuple(g) for g in got] == [tuple(w) for w in want]
+
+
+def test_refine_space_matches_oracle():
+    rng = random.Random(23)
+    checked = 0
+    for _ in range(600):
+        cls = rng.randrange(S.NUM_CLASSES)
+        rec = random_record(rng, cls)
+        if not S.record_is_well_formed(rec):
+            with pytest.raises(api.TTError):
+                api.tt_refine_space(to_c_record(rec))
+            continue
+        want = S.refine_neighbours(rec)
+        got = [r.knobs() for r in api.tt_refine_space(to_c_record(rec))]
+        key = lambda r: tuple(r[f] for f in S.RECORD_FIELDS)
+        assert sorted(map(key, got)) == sorted(map(key, want)), rec
+        assert len(set(map(key, got))) == len(got)
+        checked += 1
+    assert checked > 200

@@ -281,6 +281,90 @@ def test_selection_on_a_hand_made_time_matrix():
     assert S.select(kc, pc, pair, default, allow_slower_than_default=True)[1] == (0, 7.0, 3, 0)
 
 
+def test_selection_leaves_untried_pairs_out_of_both_counts():
+    kc, pc = [1, 1], [1, 1, 1]
+    pair = [[5.0, S.NOT_TRIED, -1.0], [S.NOT_TRIED, S.NOT_TRIED, S.NOT_TRIED]]
+    assert S.select(kc, pc, pair, [6.0, 2.0]) == [(0, 5.0, 1, 1), (-1, 2.0, 0, 0)]
+
+
+# ---- cheaper sweeps (Sections 5.5, 4.4.2) and refinement (Section 6) ------------------------------
+def test_splitmix64_reference_values():
+    """First outputs of SplitMix64 from state 0 (the values every published implementation prints) and from
+    the state 1234567: the generator advances its state by the golden-ratio constant before each output,
+    so output number n of seed s is splitmix64(s + (n - 1) * gamma)."""
+    gamma = 0x9E3779B97F4A7C15
+    want0 = [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    assert [S.splitmix64((n * gamma) & S.MASK64) for n in range(3)] == want0
+    want = [6457827717110365317, 3203168211198807973, 9817491932198370423]
+    assert [S.splitmix64((1234567 + n * gamma) & S.MASK64) for n in range(3)] == want
+
+
+def test_sweep_plan_budget_and_priority_rules():
+    kc = [1, 1, 2, 4]
+    pc = [1, 1, 0, 4, 1, 2, 1]
+    weights = [10.0, 30.0, 30.0, 5.0]
+    same = [(k, p) for k in range(4) for p in range(7) if pc[p] == kc[k]]
+    assert len(same) == 4 + 4 + 1 + 1
+    def picked(mask):
+        return [(k, p) for k in range(4) for p in range(7) if mask[k][p]]
+    # no budget, or one that covers everything: every same-class pair and nothing else
+    for budget in (0, -1, 10, 99):
+        assert picked(S.sweep_plan(kc, weights, pc, budget, False, 7)) == same
+    # a budget keeps exactly that many same-class pairs: the ones with the smallest keys
+    for budget in range(1, 10):
+        got = picked(S.sweep_plan(kc, weights, pc, budget, False, 7))
+        assert len(got) == budget and set(got) <= set(same)
+        keys = sorted((S.splitmix64(7 + k * 7 + p + 1), k * 7 + p) for k, p in same)
+        assert sorted(k * 7 + p for k, p in got) == sorted(i for _, i in keys[:budget])
+        # nested: a larger budget only adds pairs
+        assert set(got) <= set(picked(S.sweep_plan(kc, weights, pc, budget + 1, False, 7)))
+    assert picked(S.sweep_plan(kc, weights, pc, 5, False, 7)) != picked(S.sweep_plan(kc, weights, pc, 5, False, 8))
+    # priority: kernel 1 (weight 30, lower index than kernel 2) is served first, then 2, then 0, then 3
+    got = picked(S.sweep_plan(kc, weights, pc, 4, True, 7))
+    assert got == [(1, 0), (1, 1), (1, 4), (1, 6)]
+    got = picked(S.sweep_plan(kc, weights, pc, 5, True, 7))
+    assert got == [(1, 0), (1, 1), (1, 4), (1, 6), (2, 5)]
+    got = picked(S.sweep_plan(kc, weights, pc, 7, True, 7))
+    assert [q for q in got if q[0] != 0] == [(1, 0), (1, 1), (1, 4), (1, 6), (2, 5)] and len(got) == 7
+    assert sum(1 for q in got if q[0] == 0) == 2 and all(q[0] != 3 for q in got)
+
+
+def test_uniform_sampling_is_close_to_uniform():
+    """Each of 200 same-class pairs is kept about budget/total of the time over 400 seeds (a biased key, an
+    index reused as a key or a sort on the wrong field would fail this)."""
+    kc, pc = [0] * 10, [0] * 20
+    hits = [0] * 200
+    for seed in range(400):
+        m = S.sweep_plan(kc, None, pc, 50, False, seed * 1000)
+        for k in range(10):
+            for p in range(20):
+                hits[k * 20 + p] += m[k][p]
+    assert sum(hits) == 400 * 50
+    assert min(hits) > 60 and max(hits) < 145   # mean 100, sd 8.7: six sigma
+
+
+def test_refinement_neighbourhood_by_hand():
+    base = S.record(E, S.SK_MFMA, 64, 64, 32, 32, 32, 16, 2, 1, 4, 8, 2)
+    near = S.refine_neighbours(base)
+    def has(**ch):
+        return dict(base, **ch) in near
+    assert all(S.record_is_well_formed(r) for r in near) and base not in near
+    assert all(sum(1 for f in S.RECORD_FIELDS if r[f] != base[f]) == 1 for r in near)
+    assert has(tile_m=128) and has(tile_m=32) and has(tile_n=128) and has(tile_k=64) and has(tile_k=16)
+    assert has(wave_m=64) and has(wave_m=16) and has(wave_n=16)
+    assert has(mfma=32) and has(split_k=1) and has(split_k=3) and not has(split_k=4)
+    assert all(has(order=o) for o in (0, 2, 3, 4, 5)) and has(stages=1) and has(stages=3) and has(unroll=1)
+    assert has(vec=8) and has(vec=2)
+    # 5 orders + 2 stages + unroll + mfma + 2 splits + 2 vec + tile_m 2 + tile_n 2 + tile_k 2 + wave_m 2 + wave_n 2
+    assert len(near) == 5 + 2 + 1 + 1 + 2 + 2 + 2 + 2 + 2 + 2 + 2
+    # at the edges of the record format steps fall away: 16-wide tiles cannot shrink, a 32-block cannot halve its wave
+    small = S.record(E, S.SK_MFMA, 32, 32, 16, 32, 32, 32, 1, 0, 1, 1, 1)
+    near = S.refine_neighbours(small)
+    assert dict(small, wave_m=16) not in near and dict(small, tile_k=8) not in near and dict(small, stages=0) not in near
+    assert dict(small, split_k=2) in near and dict(small, vec=2) in near and dict(small, unroll=8) in near
+    assert S.refine_neighbours(S.record(E, S.SK_DIRECT, 1, 1, 1, 1, 1, 0, 1, 0, 1, 1, 1)) == []
+
+
 def parse_table2():
     models, pairs, kernels, r18 = {}, [], {}, {}
     for ln in lines("table2_model_classes.txt"):
