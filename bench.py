@@ -3,16 +3,21 @@
 
 A step is one network-shaped pass over the workload's fused kernels, each under the best
 TRANSFERRED schedule (the fastest valid donor record of its class, or the default as fallback),
-with all inputs resident in HBM.  `value` is the pass's algorithmic FLOPs over its time.  The same
-run re-times, per kernel, the record an exhaustive native sweep found and reports the transferred
-schedule's speed as a fraction of it.
+with all inputs resident in HBM and every launch of the pass on tensors of its own (a network's
+layers do not share weights or activations; the pass touches far more than the caches hold, so
+every launch finds its operands cold).  `value` is the pass's algorithmic FLOPs over its time; the
+time of the same launches repeated on one set of tensors per kernel is reported beside it as the
+cache-warm figure.  The same run re-times, per kernel, the record an exhaustive native sweep found
+and reports the transferred schedule's speed as a fraction of it.
 
-The sweeps themselves (native tuning of the donor kernels, the transfer sweep, the native sweep of
-the targets) are the search, not the step.  `--sweep` runs them here and stores their outcome next
-to the package (tuned/<workload>.json and .pool); without it the stored outcome is used, or, if
-there is none, the sweeps run first.
+The sweeps are the search, not the step.  The records the timed pass uses are the stored outcome of
+`--sweep` (tuned/<workload>.json, with the donor pool in tuned/<workload>.pool), the same records
+the parity tests check.  After the timed region the default run repeats the transfer sweep and the
+native sweep live, so their pair counts and wall-clock (the paper's "search time") are measured in
+this run; `--no-live-sweep` leaves that out (used for profiles, so that a kernel trace of the
+command holds the launches of the pass and of the per-kernel timing only).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--sweep] [--no-live-sweep]
 """
 import argparse
 import json
@@ -42,6 +47,10 @@ def parse():
     ap.add_argument("--donor-limit", type=int, default=0, help="use only the first N donor kernels")
     ap.add_argument("--level", type=int, default=1, help="size of the enumerated native space (0, 1, 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-live-sweep", action="store_true", help="do not repeat the sweeps after the timed region")
+    ap.add_argument("--kernels", default="", help="comma-separated kernel names: restrict the workload to them")
+    ap.add_argument("--cold-mb", type=int, default=600,
+                    help="per-kernel timing rotates over tensor sets of at least this many MB in total")
     ap.add_argument("--chain", action="store_true",
                     help="cfg5 only: time the bottleneck blocks wired output-to-input against the same launches on "
                          "independent tensors and against the sum of standalone times (prints its own JSON line)")
@@ -61,8 +70,9 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
             donors = donors[:args.donor_limit]
         log(f"[pool] native-tuning {len(donors)} donor kernels")
         t0 = time.time()
-        pool = tune.tune_donors(donors, cfg + 100, args.level, log)
-        tune.save_pool(pool_path, pool, [k.name for k in donors])
+        per_donor = 4 if args.workload == "cfg1" else 1
+        pool = tune.tune_donors(donors, cfg + 100, args.level, log, per_donor)
+        tune.save_pool(pool_path, pool, [donors[i // per_donor].name for i in range(len(pool))])
         pool_seconds = time.time() - t0
     else:
         pool = tune.load_pool(pool_path)
@@ -174,6 +184,65 @@ def cpu_baseline_leg(wl, targets, budget_s=25.0):
                        f"{secs:.1f} s")
 
 
+def clone_kernel(api, k, dk, use_count=1):
+    """The same kernel on fresh copies of its activations, residual and output (weights and bias too: a
+    network's layers do not share them)."""
+    tensors = {name: t.clone() for name, t in dk.tensors.items()}
+    return api.DeviceKernel(k.cls, k.shape, tensors, use_count, k.name, dk.ws.numel())
+
+
+def live_sweeps(args, api, tune, targets, dks, pool, by_name):
+    """The search, measured in this run: transfer sweep over the whole pool, native sweep of every target,
+    and the cheaper variants (pair budget, priority, local refinement)."""
+    t0 = time.time()
+    rows, table, evals, wall = api.tt_transfer_sweep(dks, pool, api.make_opts(**tune.FULL))
+    same = sum(1 for k, r in zip(targets, rows) if r["chosen"] == by_name[k.name]["chosen_pool_index"])
+    total_us = sum(r["best_us"] * k.use_count for k, r in zip(targets, rows))
+    default_total_us = sum(r["default_us"] * k.use_count for k, r in zip(targets, rows))
+    out = dict(swept_in_this_run=True, pairs=evals, wall_seconds=wall,
+               invalid_pairs=sum(r["n_invalid"] for r in rows), pool_records=len(pool),
+               kernels_on_default_fallback=sum(1 for r in rows if r["chosen"] < 0),
+               kernels_with_the_stored_choice=same, pass_us_by_standalone_times=total_us,
+               untuned_pass_us_by_standalone_times=default_total_us)
+    log(f"[live] transfer sweep: {evals} pairs in {wall:.2f}s, {out['invalid_pairs']} invalid, "
+        f"{out['kernels_on_default_fallback']} kernels on the default, {same}/{len(targets)} choices as stored")
+    # cheaper sweeps: a quarter of the donor evaluations, sampled uniformly / spent by share of untuned time
+    donor_pairs = evals - len(dks)
+    cheaper = {}
+    for name, prio in (("uniform_quarter", 0), ("priority_quarter", 1)):
+        r2, _, e2, w2 = api.tt_transfer_sweep(dks, pool, api.make_opts(pair_budget=max(1, donor_pairs // 4),
+                                                                       prioritise=prio, seed=2022, **tune.FULL))
+        us2 = sum(r["best_us"] * k.use_count for k, r in zip(targets, r2))
+        cheaper[name] = dict(pairs=e2, wall_seconds=w2, pass_us_by_standalone_times=us2,
+                             speed_vs_full_sweep=total_us / us2)
+        log(f"[live] {name}: {e2} pairs in {w2:.2f}s, pass {us2:.1f} us vs {total_us:.1f} us with the full sweep")
+    # local refinement of the transferred record, one round
+    t1 = time.time()
+    refined_us, tried = 0.0, 0
+    for k, dk, r in zip(targets, dks, rows):
+        base = pool[r["chosen"]] if r["chosen"] >= 0 else api.tt_schedule_default(k.cls, k.shape)
+        rc, best, best_us, base_us, n = api.tt_refine(dk, base, 1, api.make_opts(**tune.FULL))
+        refined_us += (best_us if rc == api.TT_OK else r["best_us"]) * k.use_count
+        tried += n
+    cheaper["refine_one_round"] = dict(pairs=tried, wall_seconds=time.time() - t1,
+                                       pass_us_by_standalone_times=refined_us, speed_vs_full_sweep=total_us / refined_us)
+    log(f"[live] refinement: {tried} pairs in {time.time() - t1:.2f}s, pass {refined_us:.1f} us")
+    out["cheaper_sweeps"] = cheaper
+    # the native (exhaustive) sweep of every target: the denominator of "% of the native optimum"
+    t2 = time.time()
+    ratios = []
+    for k, dk, r in zip(targets, dks, rows):
+        best, best_us, default_us, n_valid, n_rec = tune.native_sweep(dk, args.level)
+        ratios.append(min(best_us, r["best_us"]) / r["best_us"])
+    out["native_wall_seconds"] = time.time() - t2
+    out["pct_of_native_optimum_by_sweep_times"] = dict(mean=100.0 * sum(ratios) / len(ratios), min=100.0 * min(ratios),
+                                                       kernels_at_or_above_80pct=sum(x >= 0.8 for x in ratios))
+    out["total_seconds"] = time.time() - t0
+    log(f"[live] native sweep of {len(targets)} kernels in {out['native_wall_seconds']:.1f}s; transferred vs native: "
+        f"mean {out['pct_of_native_optimum_by_sweep_times']['mean']:.1f} %, min {out['pct_of_native_optimum_by_sweep_times']['min']:.1f} %")
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -192,7 +261,12 @@ def main():
     tuned_path = os.path.join(tuned_dir, f"{args.workload}.json")
     pool_path = os.path.join(tuned_dir, f"{args.workload}.pool")
 
-    dks = [harness.device_kernel(k, wl.seed_for(cfg, i), max_split=8) for i, k in enumerate(targets)]
+    seeds = [wl.seed_for(cfg, i) for i in range(len(targets))]
+    if args.kernels:
+        keep = [i for i, k in enumerate(targets) if k.name in args.kernels.split(",")]
+        assert keep and not args.sweep, "--kernels names no kernel of the workload (and cannot be combined with --sweep)"
+        targets, seeds = [targets[i] for i in keep], [seeds[i] for i in keep]
+    dks = [harness.device_kernel(k, sd, max_split=8) for k, sd in zip(targets, seeds)]
     if args.sweep or not os.path.exists(tuned_path):
         tuned = run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_path)
         swept_here = True
@@ -209,41 +283,48 @@ def main():
         chain_leg(args, api, harness, tune, wl, targets, dks, transfer)
         return
 
-    # ---- timed region: K network-shaped passes under the transferred schedules ----
-    klist = api.KernelList(dks, transfer)
+    # ---- timed region: K network-shaped passes under the transferred schedules, every launch on tensors
+    # of its own (kernel i's use_count launches included), in network order of the kernel list ----
+    launch_dks, launch_recs = [], []
+    for k, dk, tr in zip(targets, dks, transfer):
+        for u in range(k.use_count):
+            launch_dks.append(api.DeviceKernel(k.cls, k.shape, dk.tensors, 1, k.name, dk.ws.numel()) if u == 0
+                              else clone_kernel(api, k, dk))
+            launch_recs.append(tr)
+    cold_list = api.KernelList(launch_dks, launch_recs)
     pass_flops = sum(k.flops() * k.use_count for k in targets)
-    klist.run(args.warmup)
+    pass_bytes = sum(k.algorithmic_bytes() * k.use_count for k in targets)
+    cold_list.run(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    klist.run(args.steps)
+    cold_list.run(args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     value = pass_flops / (elapsed / args.steps) / 1e12
+    # the same launches with each kernel's use_count launches repeated on ONE set of tensors (cache-warm)
+    warm_steps = max(3, args.steps // 5)
+    warm_list = api.KernelList(dks, transfer)
+    warm_list.run(2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    warm_list.run(warm_steps)
+    torch.cuda.synchronize()
+    warm_ms = (time.perf_counter() - t0) * 1e3 / warm_steps
+    del cold_list, launch_dks
+    torch.cuda.empty_cache()
 
-    # ---- per-kernel durations with HIP events on the launch stream, and the same-run comparison with the
-    # record the native sweep found.  Every launch this process makes is entered in a ledger per kernel
-    # symbol, so the average duration reported for the dominant symbol is the one a kernel trace of this
-    # same command shows.
+    # ---- per-kernel durations with HIP events on the launch stream, cold: a kernel is launched in turn on
+    # enough tensor sets that a set has left the caches (256 MB memory-side cache, 32 MB of L2) before its
+    # turn comes again.  Every launch this process makes is entered in a ledger per kernel symbol, so the
+    # average duration reported for the dominant symbol is the one a kernel trace of this same command
+    # (with --no-live-sweep) shows.
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ledger = {}
-    reps = 10
 
     def symbol_of(k, rec):
         rec = rec if rec is not None else api.tt_schedule_default(k.cls, k.shape)
         return api.variant_name(api.tt_schedule_apply(rec, k.cls, k.shape), k.shape)
-
-    def timed_launches(k, dk, rec):
-        """Average duration of one launch of (kernel, record): use_count x reps launches between two events."""
-        one = api.KernelList([dk], [rec])
-        one.run(2)
-        e0.record()
-        one.run(reps)
-        e1.record()
-        e1.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / (reps * k.use_count)
-        book(k, rec, (reps + 2) * k.use_count, us)
-        return us
 
     def book(k, rec, launches, us):
         g = ledger.setdefault(symbol_of(k, rec), dict(us=0.0, flops=0.0, bytes=0.0, launches=0, dtype=k.shape.dtype,
@@ -254,32 +335,74 @@ def main():
         g["launches"] += launches
         g["layers"].add(k.name)
 
+    def cold_launches(k, sets, rec, rounds=3):
+        """Average duration of a launch of (kernel, record) over `rounds` turns through the tensor sets."""
+        ring = api.KernelList(sets, [rec] * len(sets))
+        ring.run(1)
+        e0.record()
+        ring.run(rounds)
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (rounds * len(sets))
+        book(k, rec, (rounds + 1) * len(sets), us)
+        return us
+
     per_kernel = []
     for k, dk, tr, na in zip(targets, dks, transfer, native):
-        t_us = timed_launches(k, dk, tr)
-        book(k, tr, (args.warmup + args.steps) * k.use_count, t_us)  # the passes of the timed region
+        n_sets = int(min(400, max(2, -(-args.cold_mb * 1e6 // k.algorithmic_bytes()) + 1)))
+        sets = [api.DeviceKernel(k.cls, k.shape, dk.tensors, 1, k.name, dk.ws.numel())]
+        sets += [clone_kernel(api, k, dk) for _ in range(n_sets - 1)]
+        t_us = cold_launches(k, sets, tr)
+        book(k, tr, (args.warmup + args.steps) * k.use_count, t_us)  # the cold passes of the timed region
         same = (tr is None and na is None) or (tr is not None and na is not None and tr.knobs() == na.knobs())
-        n_us = t_us if same else timed_launches(k, dk, na)
+        n_us = t_us if same else cold_launches(k, sets, na)
         e = by_name[k.name]
         per_kernel.append(dict(name=k.name, transfer_us=t_us, native_us=n_us, default_us_at_sweep=e["default_us"],
                                frac_of_native=min(n_us, t_us) / t_us, tflops=k.flops() / t_us / 1e6,
-                               gbps=k.algorithmic_bytes() / t_us / 1e3, kernel=symbol_of(k, tr)))
+                               gbps=k.algorithmic_bytes() / t_us / 1e3, kernel=symbol_of(k, tr), tensor_sets=n_sets,
+                               on_default_fallback=tr is None))
+        del sets
+        torch.cuda.empty_cache()
     fracs = [p["frac_of_native"] for p in per_kernel]
 
-    dom_name, dom = max(ledger.items(), key=lambda kv: kv[1]["us"])
+    # the dominant kernel symbol: the one with the largest share of a pass (use counts x cold durations)
+    share = {}
+    for p, k in zip(per_kernel, targets):
+        g = share.setdefault(p["kernel"], dict(us=0.0, flops=0.0, bytes=0.0, launches=0))
+        g["us"] += p["transfer_us"] * k.use_count
+        g["flops"] += k.flops() * k.use_count
+        g["bytes"] += k.algorithmic_bytes() * k.use_count
+        g["launches"] += k.use_count
+    dom_name, in_pass = max(share.items(), key=lambda kv: kv[1]["us"])
+    dom = ledger[dom_name]
     ridge_peak = PEAK["mfma_bf16"] if dom["dtype"] == wl.BF16 else PEAK["mfma_f32"]
-    ai = dom["flops"] / dom["bytes"]
+    ai = in_pass["flops"] / in_pass["bytes"]
     if ai >= ridge_peak * 1e12 / (PEAK["hbm"] * 1e9):
-        roof = dict(bound="mfma", achieved=dom["flops"] / dom["us"] / 1e6, peak=ridge_peak, unit="TFLOP/s")
+        roof = dict(bound="mfma", achieved=in_pass["flops"] / in_pass["us"] / 1e6, peak=ridge_peak, unit="TFLOP/s")
     else:
-        roof = dict(bound="hbm", achieved=dom["bytes"] / dom["us"] / 1e3, peak=PEAK["hbm"], unit="GB/s")
+        roof = dict(bound="hbm", achieved=in_pass["bytes"] / in_pass["us"] / 1e3, peak=PEAK["hbm"], unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["share_of_pass"] = in_pass["us"] / sum(g["us"] for g in share.values())
+    roof["launches_per_pass"] = in_pass["launches"]
     # HBM bytes per launch measured with rocprofv3 counters (paper_2201_05587_amd/traffic.py), reported
     # only while the kernel sources are the ones the counters were taken on
     roof["traffic"] = traffic.lookup(args.workload, dom_name)
-    roof.update(kernel=dom_name, avg_launch_us=dom["us"] / dom["launches"], launches=dom["launches"],
-                layers=sorted(dom["layers"]), arithmetic_intensity=ai)
+    roof.update(kernel=dom_name, avg_launch_us=in_pass["us"] / in_pass["launches"],
+                avg_launch_us_all_launches_of_this_process=dom["us"] / dom["launches"], launches=dom["launches"],
+                layers=sorted(dom["layers"]), arithmetic_intensity=ai, timing="cold: every launch on tensors that have left the caches")
     groups = {n: dict(g, layers=sorted(g["layers"]), avg_us=g["us"] / g["launches"]) for n, g in ledger.items()}
+    # the matrix-core-bound layers (arithmetic intensity above the ridge) against the MFMA peak
+    mfma_bound = [dict(name=p["name"], tflops=p["tflops"], frac_of_mfma_peak=p["tflops"] / ridge_peak)
+                  for p, k in zip(per_kernel, targets)
+                  if k.flops() / k.algorithmic_bytes() >= ridge_peak * 1e12 / (PEAK["hbm"] * 1e9)]
+
+    sweep = {"swept_in_this_run": False, "pairs": tuned["transfer_pairs"], "wall_seconds": tuned["transfer_wall_seconds"],
+             "invalid_pairs": tuned["transfer_invalid_pairs"], "native_wall_seconds": tuned["native_wall_seconds"],
+             "pool_records": tuned["pool_records"]}
+    if swept_here:
+        sweep["swept_in_this_run"] = True
+    elif not args.no_live_sweep and not args.kernels:
+        sweep = live_sweeps(args, api, tune, targets, dks, tune.load_pool(pool_path), by_name)
 
     out = {
         "metric": "fused-op TFLOP/s of best transferred schedule; % of native-swept optimum",
@@ -287,12 +410,18 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if targets[0].shape.dtype == wl.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {len(targets)} fused kernels, {sum(k.use_count for k in targets)} "
-                               f"launches per pass, {pass_flops / 1e9:.1f} GFLOP per pass",
-                   "pool_records": tuned["pool_records"], "swept_in_this_run": swept_here},
+                               f"launches per pass, {pass_flops / 1e9:.1f} GFLOP and {pass_bytes / 1e6:.0f} MB of "
+                               f"compulsory traffic per pass; tensors channels-last (NHWC activations, KRSC filters)",
+                   "pool_records": tuned["pool_records"], "swept_in_this_run": sweep["swept_in_this_run"],
+                   "kernels_on_default_fallback": sum(1 for t in transfer if t is None)},
+        "cold": {"ms_per_step": ms_per_step, "tflops": value,
+                 "what": "every launch of a pass on tensors of its own (the headline)"},
+        "warm": {"ms_per_step": warm_ms, "tflops": pass_flops / warm_ms / 1e9,
+                 "what": "each kernel's use_count launches repeated on one set of tensors"},
         "pct_of_native_optimum": {"mean": 100.0 * sum(fracs) / len(fracs), "min": 100.0 * min(fracs),
                                   "kernels_at_or_above_80pct": sum(f >= 0.8 for f in fracs), "kernels": len(fracs)},
-        "sweep": {"pairs": tuned["transfer_pairs"], "wall_seconds": tuned["transfer_wall_seconds"],
-                  "invalid_pairs": tuned["transfer_invalid_pairs"], "native_wall_seconds": tuned["native_wall_seconds"]},
+        "mfma_bound_layers": mfma_bound,
+        "sweep": sweep,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -8,6 +8,9 @@ Usage (on a GPU machine, from the repository root; each counter needs a run of its o
     rocprofv3 --pmc WRITE_SIZE -d OUT/copy_write -o run --output-format csv -- python3 -m paper_2201_05587_amd.traffic copy
     python3 -m paper_2201_05587_amd.traffic summarise OUT cfg5
 
+Any other counters (matrix-core utilisation, LDS conflicts, latencies) of the same command are tabulated
+per kernel symbol with ``python3 -m paper_2201_05587_amd.traffic counters OUT/<run> [OUT/<run> ...]``.
+
 ``copy`` launches a device-to-device copy of a known size, so the counters' unit
 can be checked against bytes that certainly crossed HBM: the calibration
 factor is known bytes / counter reading.  ``summarise`` averages each counter
@@ -135,9 +138,34 @@ def lookup(workload: str, symbol: str):
     return k["fetch_bytes_per_launch"] + k["write_bytes_per_launch"]
 
 
+def counters_table(directories) -> str:
+    """Per kernel symbol of this library: the mean of every counter found under the given output
+    directories (one rocprofv3 --pmc run each), and the number of dispatches it was averaged over."""
+    acc = {}
+    names = []
+    for d in directories:
+        for r in _rows(d):
+            s = _symbol(r["Kernel_Name"])
+            if "tt::" not in s:
+                continue
+            c = r["Counter_Name"]
+            if c not in names:
+                names.append(c)
+            tot, n = acc.setdefault(s, {}).get(c, (0.0, 0))
+            acc[s][c] = (tot + float(r["Counter_Value"]), n + 1)
+    lines = ["# symbol | dispatches | " + " | ".join(names)]
+    for s in sorted(acc, key=lambda s: -max(n for _, n in acc[s].values())):
+        n = max(n for _, n in acc[s].values())
+        cells = [f"{acc[s][c][0] / acc[s][c][1]:.4g}" if c in acc[s] else "-" for c in names]
+        lines.append(f"{s.replace('tt::', '')} | {n} | " + " | ".join(cells))
+    return "\n".join(lines) + "\n"
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 2 and sys.argv[1] == "copy":
         run_copy()
+    elif len(sys.argv) >= 3 and sys.argv[1] == "counters":
+        sys.stdout.write(counters_table(sys.argv[2:]))
     elif len(sys.argv) >= 4 and sys.argv[1] == "summarise":
         print(summarise(sys.argv[2], sys.argv[3]))
     else:

@@ -38,13 +38,47 @@ def native_sweep(dk: api.DeviceKernel, level: int = 1, finalists: int = 4):
     return (None if best.knobs() == default.knobs() else best), best_us, default_us, n_valid, n_rec
 
 
-def tune_donors(kernels: Sequence[wl.Kernel], seed_cfg: int, level: int = 1, log=None) -> List[api.tt_schedule]:
-    """Native-tune every donor kernel; each contributes its optimum as one pool record."""
+def fastest_distinct_tiles(dk: api.DeviceKernel, level: int, count: int, tiles=(32, 64, 128)):
+    """The `count` fastest records of the class's space on this kernel whose workgroup tiles come from
+    `tiles` and differ pairwise in (tile_m, tile_n, tile_k): a small donor pool from one tuned kernel."""
+    space = [r for r in api.tt_schedule_space(dk.cls, dk.cshape.dtype, level)
+             if r.sketch == api.TT_SK_MFMA and r.tile_m in tiles and r.tile_n in tiles and r.tile_k in tiles]
+    _, table, _, _ = api.tt_transfer_sweep([dk], space, api.make_opts(**EXPLORE))
+    ranked = sorted((t, i) for i, t in enumerate(table[0]) if t >= 0)
+    top, seen = [], set()
+    for _, i in ranked:
+        key = (space[i].tile_m, space[i].tile_n, space[i].tile_k)
+        if key not in seen:
+            seen.add(key)
+            top.append(space[i])
+        if len(top) == 3 * count:
+            break
+    _, table, _, _ = api.tt_transfer_sweep([dk], top, api.make_opts(**FULL))
+    ranked = sorted((t, i) for i, t in enumerate(table[0]) if t >= 0)[:count]
+    return [(top[i].copy(), t) for t, i in ranked]
+
+
+def tune_donors(kernels: Sequence[wl.Kernel], seed_cfg: int, level: int = 1, log=None,
+                records_per_donor: int = 1) -> List[api.tt_schedule]:
+    """Native-tune every donor kernel; each contributes its optimum as one pool record (or, with
+    records_per_donor > 1, its fastest records of pairwise distinct workgroup tiles)."""
     import torch
     pool: List[api.tt_schedule] = []
     for i, k in enumerate(kernels):
         dk = harness.device_kernel(k, wl.seed_for(seed_cfg, i), max_split=8)
         t0 = time.time()
+        if records_per_donor > 1:
+            for rec, us in fastest_distinct_tiles(dk, level, records_per_donor):
+                rec.id = len(pool)
+                for j, v in enumerate(shape_ints(k.shape)):
+                    rec.donor_shape[j] = v
+                rec.donor_us = us
+                pool.append(rec)
+                if log:
+                    log(f"donor {i:3d} {k.name:34s} {us:9.2f} us  {rec}")
+            del dk
+            torch.cuda.empty_cache()
+            continue
         best, best_us, default_us, n_valid, n_rec = native_sweep(dk, level)
         if best is None:
             best = api.tt_schedule_default(k.cls, k.shape)
@@ -111,6 +145,7 @@ def choose_donor_pool(targets: Sequence[wl.Kernel], default_us: Sequence[float],
 def workload(name: str):
     """(cfg index, target kernels, donor kernels) of a named configuration."""
     if name == "cfg1":
+        # one donor kernel; its pool holds its 4 fastest records of distinct tiles from {32, 64, 128}^3
         return 1, [wl.cfg1_target()], [wl.cfg1_donor()]
     if name == "cfg2":
         return 2, wl.resnet18_kernels(1, wl.F32), wl.resnet50_kernels(1, wl.F32)

@@ -415,3 +415,54 @@ def test_transfer_sweep_on_cfg1(api, P):
     # the chosen record still computes the right thing
     chosen = rows[0]["chosen"]
     P.check_kernel(target, [pool[chosen] if chosen >= 0 else None], seed=11)
+
+
+def test_budgeted_sweep_evaluates_the_planned_pairs_only(api, P):
+    """A pair budget: every default is timed, then exactly the pairs tt_sweep_plan selects (the oracle's rule)."""
+    from paper_2201_05587_amd import harness
+    target, donor = wl.cfg1_target(), wl.cfg1_donor()
+    E = target.cls
+    pool = [mfma(api, E, 32, 32, 32, 16, 16, 16), mfma(api, E, 64, 64, 32, 32, 32, 32), mfma(api, E, 128, 64, 32, 64, 32, 32),
+            mfma(api, wl.CLS_CONV2D_ADD, 32, 32, 32, 16, 16, 16), mfma(api, E, 64, 32, 32, 32, 32, 16),
+            mfma(api, E, 32, 64, 32, 32, 32, 16)]
+    dks = [harness.device_kernel(target, 11), harness.device_kernel(donor, 12)]
+    for prio in (0, 1):
+        rows, table, evals, _ = api.tt_transfer_sweep(dks, pool, api.make_opts(warmup=1, samples=3, pair_budget=4,
+                                                                               prioritise=prio, seed=99))
+        assert evals == 2 + 4
+        weights = [r["default_us"] * 1 for r in rows]
+        want = S.sweep_plan([E, E], weights, [p.cls for p in pool], 4, bool(prio), 99)
+        for k in range(2):
+            for p in range(len(pool)):
+                if pool[p].cls != E:
+                    assert table[k][p] == -2.0
+                elif want[k][p]:
+                    assert table[k][p] > 0 or table[k][p] == -1.0
+                else:
+                    assert table[k][p] == -3.0
+            assert rows[k]["n_not_tried"] == sum(1 for p in range(len(pool)) if pool[p].cls == E and not want[k][p])
+            tried = [table[k][p] for p in range(len(pool)) if table[k][p] > 0]
+            assert rows[k]["best_us"] == min(tried + [rows[k]["default_us"]])
+
+
+def test_refinement_and_native_sweep_return_records_that_compute_the_operator(api, P):
+    from paper_2201_05587_amd import harness
+    k = conv_kernel(wl.CLS_CONV2D_BIAS_RELU, 2, 64, 28, 64, 3, 1, dtype=wl.BF16)
+    dk = harness.device_kernel(k, 5, max_split=8)
+    base = mfma(api, k.cls, 32, 32, 32, 16, 16, 16, stages=2)
+    quick = api.make_opts(warmup=1, samples=3, min_sample_us=50, max_launches=8)
+    rc, best, best_us, base_us, tried = api.tt_refine(dk, base, 2, quick)
+    assert rc == api.TT_OK and 0 < best_us <= base_us and tried >= 10
+    near = [r.knobs() for r in api.tt_refine_space(base)]
+    assert best.knobs() == base.knobs() or best_us < base_us
+    if best.knobs() != base.knobs() and best.knobs() not in near:
+        # two rounds: a neighbour of a neighbour
+        assert any(best.knobs() in [q.knobs() for q in api.tt_refine_space(api.make_schedule(**n))] for n in near)
+    # a base that does not apply is refused, nothing timed
+    bad = mfma(api, k.cls, 256, 256, 32, 64, 64, 16)
+    assert api.tt_refine(dk, bad, 1, quick)[0] == api.TT_ERR_INVALID_SCHEDULE
+    nbest, nbest_us, default_us, n_valid, n_rec = api.tt_native_sweep(dk, 0, 3, quick, quick)
+    assert 0 < nbest_us <= default_us and 0 < n_valid <= n_rec
+    plan = api.tt_schedule_apply(nbest, k.cls, k.shape)
+    assert plan.status == api.TT_OK and plan.variant_id >= 0
+    P.check_kernel(k, [best, nbest], seed=5)
