@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="run the sweeps and store their outcome")
     ap.add_argument("--retune-pool", action="store_true", help="also re-tune the donor kernels (the pool)")
     ap.add_argument("--donor-limit", type=int, default=0, help="use only the first N donor kernels")
+    ap.add_argument("--resume-pool", default="", help="pool checkpoint of an interrupted --retune-pool run to continue from")
     ap.add_argument("--level", type=int, default=1, help="size of the enumerated native space (0, 1, 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-live-sweep", action="store_true", help="do not repeat the sweeps after the timed region")
@@ -71,7 +72,9 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
         log(f"[pool] native-tuning {len(donors)} donor kernels")
         t0 = time.time()
         per_donor = 4 if args.workload == "cfg1" else 1
-        pool = tune.tune_donors(donors, cfg + 100, args.level, log, per_donor)
+        partial = os.path.join(ROOT, "gpurun_out", f"{args.workload}.pool.partial")
+        pool = tune.tune_donors(donors, cfg + 100, args.level, log, per_donor,
+                                partial if os.path.isdir(os.path.dirname(partial)) else None, args.resume_pool or None)
         tune.save_pool(pool_path, pool, [donors[i // per_donor].name for i in range(len(pool))])
         pool_seconds = time.time() - t0
     else:

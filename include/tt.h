@@ -131,7 +131,12 @@ typedef struct tt_gemm_shape {
  *                (Vectorize); unroll = depth to which the per-tile K-step loop is unrolled (Unroll);
  *                stages = LDS buffers (cache buffer + ComputeAt): 1 or 2 with register-staged loads,
  *                3 or 4 = ring filled by asynchronous global-to-LDS loads (reformulated to 2 where
- *                the ring does not apply: partial 16-byte items, [K][N] operands, odd tile/thread ratios).
+ *                the ring does not apply: partial 16-byte items, [K][N] operands, odd tile/thread ratios);
+ *                5 or 6 = 3x3 convolutions only: the padding stage of Algorithm 2 computed at the
+ *                workgroup tile, i.e. the tile's padded input patch cached in LDS for tile_k channels at
+ *                a time, plus a ring of 3 or 4 filter buffers (reformulated to 3 or 4 where it does
+ *                not apply: other filters or data types, a patch larger than the kernel's buffer, a
+ *                channel count tile_k does not divide, a split off the channel-slice boundaries).
  *   TT_SK_GEMV   tile_m (= wave_m) rows and tile_n outputs per workgroup, wave_n outputs per wave,
  *                tile_k = K elements a wave consumes per step (64 lanes x 1/2/4/8), mfma = 0.
  *   TT_SK_DWCONV tile_m x tile_n output rows x cols and tile_k lanes along the plane axis per workgroup,
@@ -151,7 +156,7 @@ typedef struct tt_schedule {
     int32_t order;  /* 0 M-tiles fastest, 1 N-tiles fastest, 2 bands of 8 M-tiles; +3 = XCD-contiguous */
     int32_t vec;    /* 1, 2, 4 or 8 */
     int32_t unroll; /* >= 1 */
-    int32_t stages; /* 1..4 (matrix-core sketch), 1 or 2 (others) */
+    int32_t stages; /* 1..6 (matrix-core sketch), 1 or 2 (others) */
     /* provenance (ignored by tt_schedule_apply): */
     int32_t id;              /* caller's identifier of the record                     */
     int32_t donor_shape[12]; /* the shape the record was tuned on (struct as int32[]) */
@@ -411,8 +416,10 @@ int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out, int cap);
  * {dtype, family (0 conv, 1 GEMM with [N][K] B, 2 GEMM with [K][N] B), tile_m, tile_n, tile_k, wave_m,
  * wave_n, mfma, bytes per gathered load (conv family; 0 otherwise), pipeline (0 register-staged,
  * symbol contract_kernel with the first nine arguments; 1 asynchronous ring, symbol
- * contract_async_kernel with the first eight), LDS bytes of one pipeline stage, reduction elements one
- * matrix-core step consumes (tile_k is a multiple of it)}.  TT_ERR_BAD_ARG for an id outside the table.
+ * contract_async_kernel with the first eight; 2 the 3x3 convolution kernel with the padded input patch
+ * in LDS, symbol conv3x3_patch_kernel), LDS bytes of one pipeline stage (pipeline 2: the pixels one patch
+ * buffer holds), reduction elements one matrix-core step consumes (tile_k is a multiple of it)}.
+ * TT_ERR_BAD_ARG for an id outside the table.
  */
 int tt_variant_info(int variant_id, int32_t out[12]);
 /* Number of compiled variants: ids 0 .. tt_num_variants() - 1. */

@@ -514,6 +514,12 @@ def variant_name(plan: tt_plan, shape=None) -> str:
     """
     if plan.sketch == TT_SK_MFMA:
         info = tt_variant_info(plan.variant_id)
+        if info[9] == 2:
+            threads = (info[2] // info[5]) * (info[3] // info[6]) * 128
+            per_thread = info[10] * (info[4] // 8) // threads   # patch items per thread and channel slice
+            stride = shape.stride_h if shape is not None else 0
+            return (f"tt::conv3x3_patch_kernel<{info[2]}, {info[3]}, {info[4]}, {info[5]}, {info[6]}, {stride}, "
+                    f"{per_thread}>")
         if info[9]:
             return "tt::contract_async_kernel<" + ", ".join(str(v) for v in info[:8]) + ">"
         return "tt::contract_kernel<" + ", ".join(str(v) for v in info[:9]) + ">"

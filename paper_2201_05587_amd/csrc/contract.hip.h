@@ -543,9 +543,37 @@ __device__ __noinline__ void write_row_elements(float *ws, void *out, const void
     }
 }
 
+// The bias of the 8 output columns a lane finishes in the epilogue (the same for every row), as raw
+// bits.  Requested at the start of a kernel, so that its memory latency runs under the K loop; a load
+// inside the epilogue's loops would be repeated per pass at full latency, because the compiler cannot
+// move it across the stores.  Zero where the vector path does not apply (no bias, split-K partials,
+// rows that are not whole 16-byte vectors long: that path reads the bias element by element).
+template <int DT> struct BiasRegs {
+    u32x4 raw[DT == TT_BF16 ? 1 : 2];
+};
+template <int DT, int TM, int WM, int WN, int MF>
+__device__ __forceinline__ BiasRegs<DT> load_bias_early(const ContractArgs &g, const TileCoord &tc, int wave, int lane)
+{
+    using T = TileOut<TM, WM, WN, MF>;
+    BiasRegs<DT> b;
+    b.raw[0] = u32x4{0u, 0u, 0u, 0u};
+    if constexpr (DT == TT_F32) b.raw[1] = u32x4{0u, 0u, 0u, 0u};
+    const int first = tc.n0 + T::col(wave, lane);
+    const bool whole = DT == TT_BF16 ? g.eff_vec_c == 8 : g.eff_vec_c >= 4;
+    if (whole && g.map.eff_split_k == 1 && g.has_bias && first < g.N) {
+        if constexpr (DT == TT_BF16) {
+            b.raw[0] = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + first);
+        } else {
+            b.raw[0] = *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.bias) + first);
+            if (first + 4 < g.N) b.raw[1] = *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.bias) + first + 4);
+        }
+    }
+    return b;
+}
+
 template <int DT, int TM, int WM, int WN, int MF, typename Acc>
 __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
-                                           unsigned char *smem, int wave, int lane)
+                                           unsigned char *smem, int wave, int lane, const BiasRegs<DT> &bias)
 {
     using T = TileOut<TM, WM, WN, MF>;
     constexpr int NI = T::NI, NJ = T::NJ, ACC = T::ACC, ESTRIDE = T::ESTRIDE, CG = T::CG, PASSES = T::PASSES;
@@ -561,12 +589,43 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
     const int cg = lane % CG;
     const int first = tc.n0 + T::col(wave, lane);
 
+    float biasf[8];
+    if constexpr (DT == TT_BF16) {
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            biasf[2 * h] = __uint_as_float(bias.raw[0][h] << 16);
+            biasf[2 * h + 1] = __uint_as_float(bias.raw[0][h] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) biasf[e] = __uint_as_float(bias.raw[0][e]), biasf[4 + e] = __uint_as_float(bias.raw[1][e]);
+    }
+
     // Every wave is done reading the operand tiles.  From here on a wave only touches its own staging
     // region, and the LDS executes one wave's accesses in order: no further barrier is needed, only
     // the compiler must keep the staging writes and reads in program order.
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
+        // the residuals of this band's rows: all requested before the staging, so that their latency
+        // runs in parallel instead of once per pass
+        u32x4 resv[PASSES][DT == TT_BF16 ? 1 : 2];
+        if (whole && !partial && g.has_res) {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int m = tc.m0 + T::row(wave, lane, i, ps);
+                const bool live = T::pass_live(lane, ps) && m < g.M && first < g.N;
+                const int64_t row_at = out_base + (int64_t)(live ? m : tc.m0) * g.N + (live ? first : tc.n0);
+                if constexpr (DT == TT_BF16) {
+                    resv[ps][0] = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + row_at);
+                } else {
+                    resv[ps][0] = *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.res) + row_at);
+                    resv[ps][1] = (live && first + 4 < g.N)
+                                      ? *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.res) + row_at + 4)
+                                      : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
         asm volatile("" ::: "memory"); // the reads of the band before stay ahead of these writes
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
@@ -594,20 +653,13 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                     *reinterpret_cast<f32x4 *>(ws + row_at) = lo;
                     if (DT == TT_BF16 || first + 4 < g.N) *reinterpret_cast<f32x4 *>(ws + row_at + 4) = hi;
                 } else if constexpr (DT == TT_BF16) {
-                    if (g.has_bias) {
-                        const u32x4 biasv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.bias) + first);
 #pragma unroll
-                        for (int h = 0; h < 4; ++h) {
-                            val[2 * h] += __uint_as_float(biasv[h] << 16);
-                            val[2 * h + 1] += __uint_as_float(biasv[h] & 0xffff0000u);
-                        }
-                    }
+                    for (int e = 0; e < 8; ++e) val[e] += biasf[e];
                     if (g.has_res) {
-                        const u32x4 resv = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + row_at);
 #pragma unroll
                         for (int h = 0; h < 4; ++h) {
-                            val[2 * h] += __uint_as_float(resv[h] << 16);
-                            val[2 * h + 1] += __uint_as_float(resv[h] & 0xffff0000u);
+                            val[2 * h] += __uint_as_float(resv[ps][0][h] << 16);
+                            val[2 * h + 1] += __uint_as_float(resv[ps][0][h] & 0xffff0000u);
                         }
                     }
                     apply_act_all(val, g.act);
@@ -620,11 +672,12 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                     for (int q4 = 0; q4 < 2; ++q4) {
                         if (q4 == 1 && first + 4 >= g.N) break;
                         const int64_t at = row_at + 4 * q4;
-                        f32x4 add = {0.0f, 0.0f, 0.0f, 0.0f};
-                        if (g.has_bias) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.bias) + first + 4 * q4);
-                        if (g.has_res) add += *reinterpret_cast<const f32x4 *>(static_cast<const float *>(g.res) + at);
-                        float sum[4] = {val[4 * q4] + add[0], val[4 * q4 + 1] + add[1], val[4 * q4 + 2] + add[2],
-                                        val[4 * q4 + 3] + add[3]};
+                        float sum[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            sum[e] = val[4 * q4 + e] + biasf[4 * q4 + e];
+                            if (g.has_res) sum[e] += __uint_as_float(resv[ps][q4][e]);
+                        }
                         apply_act_all(sum, g.act);
                         *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = f32x4{sum[0], sum[1], sum[2], sum[3]};
                     }
@@ -691,6 +744,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
+    const BiasRegs<DT> bias = load_bias_early<DT, TM, WM, WN, MF>(g, tc, wave, lane);
     // The gathering loaders walk the reduction in runs padded to whole 16-byte items (k_walk >= K):
     // the split that ends at K runs on to the end of that walk.
     const int k_end = (CONV && tc.k0 + tc.k_ext == g.K) ? g.k_walk : tc.k0 + tc.k_ext;
@@ -834,7 +888,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     else
         k_loop(std::false_type{});
 
-    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane);
+    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane, bias);
 }
 
 // ---- asynchronous pipeline: global -> LDS without passing through registers --------------------------------------
@@ -1004,6 +1058,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
+    const BiasRegs<DT> bias = load_bias_early<DT, TM, WM, WN, MF>(g, tc, wave, lane);
     const int k_end = tc.k0 + tc.k_ext; // (whole items only: the gather's walk is the reduction itself)
     const int kt_count = (tc.k_ext + TK - 1) / TK;
     const int bidx = tc.hi;
@@ -1155,7 +1210,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
         k_loop(std::true_type{});
     else
         k_loop(std::false_type{});
-    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane);
+    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane, bias);
 }
 
 // More than 48 KB of dynamic LDS has to be enabled per kernel.  Remembers the largest size enabled so far
@@ -1199,6 +1254,14 @@ template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int A
 template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF> int stage_bytes_contract_async()
 {
     return RingLayout<DT, TM, TN, TK>::STAGE_BYTES;
+}
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF, int AM> int lds_bytes_contract(int stages)
+{
+    return stages * StageLayout<DT, FAM, TM, TN, TK, MF>::STAGE_BYTES;
+}
+template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF> int lds_bytes_contract_async(int stages)
+{
+    return stages * RingLayout<DT, TM, TN, TK>::STAGE_BYTES;
 }
 
 template <int DT, int FAM, int TM, int TN, int TK, int WM, int WN, int MF>

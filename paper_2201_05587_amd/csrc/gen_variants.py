@@ -39,6 +39,44 @@ TILES_SMALL = [(16, 16, 16, 16), (32, 32, 16, 16), (64, 64, 32, 32), (128, 128, 
                (32, 64, 32, 32), (64, 32, 32, 32)]
 
 
+# 3x3 convolutions with the padded input patch in LDS (bf16, 32-blocks, two K groups per wave position):
+# (tile_m, tile_n, channels per slice = tile_k, wave_m, wave_n, stride, patch items per thread and slice)
+PATCH_TILES = [
+    (128, 128, 64, 64, 64, 1, 6), (128, 64, 64, 64, 32, 1, 6), (128, 64, 64, 64, 64, 1, 7), (256, 64, 64, 64, 64, 1, 7),
+    (64, 128, 64, 64, 64, 1, 7), (64, 64, 64, 64, 32, 1, 7), (64, 128, 64, 32, 64, 1, 4), (256, 128, 64, 64, 64, 1, 3),
+    (128, 128, 32, 64, 64, 1, 4),
+    (128, 128, 32, 64, 64, 2, 6), (64, 128, 32, 64, 64, 2, 7), (64, 64, 32, 64, 32, 2, 7), (128, 64, 32, 64, 64, 2, 7),
+]
+
+
+def patch_variants():
+    seen, out = set(), []
+    for tm, tn, ck, wm, wn, stride, pl in PATCH_TILES:
+        key = (tm, tn, ck, wm, wn, stride)
+        assert key not in seen, key  # one patch capacity per (tile, stride): the record does not carry it
+        seen.add(key)
+        threads = (tm // wm) * (tn // wn) * 128
+        cpp = ck // 8
+        assert (tn * cpp) % threads == 0 and (threads // 16) % cpp == 0, key  # the filter loader's conditions
+        assert (pl * threads) % cpp == 0 and pl <= 7, key
+        out.append((BF16, 0, tm, tn, ck, wm, wn, 32, 16, 2, stride, pl))
+    return out
+
+
+def spilling():
+    """(kernel name, template arguments) of the instances listed in spilling_variants.txt."""
+    import re
+    out = set()
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "spilling_variants.txt")
+    if os.path.exists(path):
+        with open(path) as f:
+            for ln in f:
+                m = re.match(r"(\w+)<(.*)>", ln.strip())
+                if m:
+                    out.add((m.group(1), tuple(int(x) for x in m.group(2).split(","))))
+    return out
+
+
 def variants(which):
     tiles = TILES_SMALL if which == "small" else TILES_FULL
     out = []
@@ -57,10 +95,13 @@ def variants(which):
                         for am in amodes:
                             if am not in (0, 16) and tk not in tks:
                                 continue  # the element-wise gather keeps much per-item state: no deep slices
-                            out.append((dt, fam, tm, tn, tk, wm, wn, mf, am, 0))
+                            out.append((dt, fam, tm, tn, tk, wm, wn, mf, am, 0, 0))
                             if async_ok(dt, fam, tm, tn, tk, wm, wn, am):
-                                out.append((dt, fam, tm, tn, tk, wm, wn, mf, am, 1))
-    return out
+                                out.append((dt, fam, tm, tn, tk, wm, wn, mf, am, 1, 0))
+    skip = spilling()
+    out = [v for v in out if not (v[9] == 0 and ("contract_kernel", v[:9]) in skip)]
+    patch = [v for v in patch_variants() if ("conv3x3_patch_kernel", (v[2], v[3], v[4], v[5], v[6], v[10], v[11])) not in skip]
+    return out + patch
 
 
 def async_ok(dt, fam, tm, tn, tk, wm, wn, am):
@@ -83,26 +124,34 @@ def main():
     for i, v in enumerate(vs):
         slices[i % n_slices].append((i, v))
     for s, items in enumerate(slices):
-        lines = ['// generated by gen_variants.py - do not edit', '#include "../contract.hip.h"', "namespace tt {"]
+        lines = ['// generated by gen_variants.py - do not edit', '#include "../contract.hip.h"',
+                 '#include "../conv_patch.hip.h"', "namespace tt {"]
         for i, v in items:
-            if v[9]:
+            if v[9] == 2:
+                args = ", ".join(str(x) for x in (v[2], v[3], v[4], v[5], v[6], v[10], v[11]))
+                call, size, lds = (f"launch_conv_patch<{args}>", f"capacity_conv_patch<{args}>",
+                                   f"lds_bytes_conv_patch<{args}>")
+            elif v[9] == 1:
                 args = ", ".join(str(x) for x in v[:8])
-                call = f"launch_contract_async<{args}>"
+                call, size, lds = (f"launch_contract_async<{args}>", f"stage_bytes_contract_async<{args}>",
+                                   f"lds_bytes_contract_async<{args}>")
             else:
                 args = ", ".join(str(x) for x in v[:9])
-                call = f"launch_contract<{args}>"
+                call, size, lds = f"launch_contract<{args}>", f"stage_bytes_contract<{args}>", f"lds_bytes_contract<{args}>"
             lines.append(f"int ttv_{i}(const ContractArgs &a, int grid, int lds, void *s) "
                          f"{{ return {call}(a, grid, lds, s); }}")
-            lines.append(f"int tts_{i}() {{ return {call.replace('launch_contract', 'stage_bytes_contract')}(); }}")
+            lines.append(f"int tts_{i}() {{ return {size}(); }}")
+            lines.append(f"int ttl_{i}(int stages) {{ return {lds}(stages); }}")
         lines.append("} // namespace tt")
         write_if_changed(os.path.join(out_dir, f"inst_{s:02d}.hip"), "\n".join(lines) + "\n")
     lines = ['// generated by gen_variants.py - do not edit', '#include "../tt_internal.h"', "namespace tt {"]
     for i, _ in enumerate(vs):
         lines.append(f"int ttv_{i}(const ContractArgs &, int, int, void *);")
         lines.append(f"int tts_{i}();")
+        lines.append(f"int ttl_{i}(int);")
     lines.append("const Variant kVariants[] = {")
     for i, v in enumerate(vs):
-        lines.append("    {" + ", ".join(str(x) for x in v) + f", ttv_{i}, tts_{i}}},")
+        lines.append("    {" + ", ".join(str(x) for x in v[:11]) + f", ttv_{i}, tts_{i}, ttl_{i}}},")
     lines.append("};")
     lines.append(f"const int kNumVariants = {len(vs)};")
     lines.append("} // namespace tt")

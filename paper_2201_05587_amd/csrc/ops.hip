@@ -173,6 +173,10 @@ extern "C" int tt_conv2d_bias_relu(const void *x, const void *w, const void *bia
     g.k_walk = shape->r * g.runp;
     g.div_hw = make_fastdiv((uint32_t)(g.Ho * g.Wo));
     g.div_wo = make_fastdiv((uint32_t)g.Wo);
+    g.PW = shape->w + 2 * shape->pad_w;
+    g.PHW = (shape->h + 2 * shape->pad_h) * g.PW;
+    g.div_phw = make_fastdiv((uint32_t)g.PHW);
+    g.div_pw = make_fastdiv((uint32_t)g.PW);
     g.a_bytes = (uint32_t)x_bytes;
     g.b_bytes = (uint32_t)w_bytes;
     int family = FAM_CONV;

@@ -73,7 +73,7 @@ bool record_well_formed(const tt_schedule &r)
     if (r.sketch < TT_SK_MFMA || r.sketch > TT_SK_DIRECT) return false;
     if (r.split_k < 1 || r.order < 0 || r.order >= 6) return false;
     if (r.vec != 1 && r.vec != 2 && r.vec != 4 && r.vec != 8) return false;
-    if (r.unroll < 1 || r.stages < 1 || r.stages > (r.sketch == TT_SK_MFMA ? 4 : 2)) return false;
+    if (r.unroll < 1 || r.stages < 1 || r.stages > (r.sketch == TT_SK_MFMA ? 6 : 2)) return false;
     switch (r.sketch) {
     case TT_SK_MFMA: {
         if (r.mfma != 16 && r.mfma != 32) return false;
@@ -107,6 +107,25 @@ bool record_well_formed(const tt_schedule &r)
         return r.mfma == 0 && r.tile_m == 1 && r.tile_n == 1 && r.tile_k == 1 && r.wave_m == 1 && r.wave_n == 1 &&
                r.split_k == 1;
     }
+}
+
+// Pixels of the padded input that the tile_m output pixels of one workgroup touch under a 3x3 filter,
+// the largest over all tiles: the index range [base(first), base(last) + 2 PW + 2] of flat padded pixel
+// indices, base(img, p, q) = img * PH * PW + p * stride * PW + q * stride.
+int64_t patch_pixels(const tt_conv_shape &s, int tile_m, int M)
+{
+    const int ho = conv_out(s.h, s.r, s.stride_h, s.pad_h), wo = conv_out(s.w, s.s, s.stride_w, s.pad_w);
+    const int64_t pw = s.w + 2 * s.pad_w, phw = (int64_t)(s.h + 2 * s.pad_h) * pw;
+    const auto base = [&](int64_t m) {
+        const int64_t img = m / ((int64_t)ho * wo), rem = m % ((int64_t)ho * wo);
+        return img * phw + (rem / wo) * s.stride_h * pw + (rem % wo) * s.stride_w;
+    };
+    int64_t worst = 0;
+    for (int64_t m0 = 0; m0 < M; m0 += tile_m) {
+        const int64_t last = std::min<int64_t>(m0 + tile_m, M) - 1;
+        worst = std::max(worst, base(last) - base(m0) + 2 * pw + 3);
+    }
+    return worst;
 }
 
 int fail(tt_plan *plan, int status, int reason)
@@ -149,12 +168,12 @@ int family_of(int cls, int trans_b)
     return FAM_GEMM_TN;
 }
 
-int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode, int pipe)
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode, int pipe, int stride)
 {
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         if (v.dtype == dtype && v.family == family && v.tile_m == tm && v.tile_n == tn && v.tile_k == tk &&
-            v.wave_m == wm && v.wave_n == wn && v.mfma == mf && v.amode == amode && v.pipe == pipe)
+            v.wave_m == wm && v.wave_n == wn && v.mfma == mf && v.amode == amode && v.pipe == pipe && v.stride == stride)
             return i;
     }
     return -1;
@@ -390,16 +409,46 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     // (the conv entry point refuses tensors of 2 GiB and more for every matrix-core record)
     const bool in_range = is_conv_class(cls) ||
                           ((int64_t)e.M * e.K * elem < (1ll << 31) && (int64_t)e.N * e.K * elem < (1ll << 31));
+    // Five or six stages ask for the 3x3 convolution kernel that keeps the padded input patch of the
+    // workgroup's tile in LDS and streams the filters through a ring of three or four buffers.  It exists
+    // for bf16, 32-blocks, equal strides of 1 or 2, channel counts that tile_k divides, splits of the
+    // reduction that fall on channel-slice boundaries, and tiles whose patch fits the compiled buffer;
+    // elsewhere the record is reformulated to the plain ring of stages - 2 buffers.
+    int want = r.stages;
+    if (want >= 5) {
+        int patch_id = -1;
+        if (is_conv_class(cls) && dt == TT_BF16 && r.mfma == 32 && whole_items && amode == 16) {
+            const tt_conv_shape *s = static_cast<const tt_conv_shape *>(shape);
+            if (s->r == 3 && s->s == 3 && s->stride_h == s->stride_w && (s->stride_h == 1 || s->stride_h == 2) &&
+                s->c % r.tile_k == 0 && p.k_iters % 9 == 0) {
+                const int id = find_variant(dt, FAM_CONV, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, 16, 2,
+                                            s->stride_h);
+                if (id >= 0 && patch_pixels(*s, r.tile_m, e.M) <= kVariants[id].stage_bytes()) patch_id = id;
+            }
+        }
+        if (patch_id >= 0) {
+            const int64_t lds = kVariants[patch_id].lds_bytes(want);
+            if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
+            p.stages = want;
+            p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
+            p.variant_id = patch_id;
+            p.lds_bytes = (int)lds;
+            *plan = p;
+            return TT_OK;
+        }
+        want -= 2;
+    }
     const int ring_id = whole_items && in_range
                             ? find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, amode, 1)
                             : -1;
-    if (r.stages >= 3 && ring_id < 0) p.stages = 2;
+    p.stages = want;
+    if (want >= 3 && ring_id < 0) p.stages = 2;
     p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
     p.variant_id = p.stages >= 3 ? ring_id
                                  : find_variant(dt, family, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma,
                                                 amode, 0);
     if (p.variant_id >= 0) {
-        const int64_t lds = (int64_t)p.stages * kVariants[p.variant_id].stage_bytes();
+        const int64_t lds = kVariants[p.variant_id].lds_bytes(p.stages);
         if (lds > kLdsBudget) return fail(plan, TT_ERR_INVALID_SCHEDULE, TT_R_LDS);
         p.lds_bytes = (int)lds;
     }
@@ -434,7 +483,8 @@ extern "C" int tt_variant_info(int variant_id, int32_t out[12])
     if (!out || variant_id < 0 || variant_id >= kNumVariants) return TT_ERR_BAD_ARG;
     const Variant &v = kVariants[variant_id];
     const int32_t vals[12] = {v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode, v.pipe,
-                              v.stage_bytes(), k_granule(v.dtype, v.mfma)};
+                              v.stage_bytes(),
+                              k_granule(v.dtype, v.mfma)};
     std::copy(vals, vals + 12, out);
     return TT_OK;
 }
@@ -664,10 +714,15 @@ extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out
             const int n_order = level >= 2 ? 6 : (level >= 1 ? 2 : 1);
             for (int si = 0; si < n_split; ++si)
                 for (int order = 0; order < n_order; ++order)
-                    for (int stages = (level >= 1 ? 1 : 2); stages <= (level >= 1 ? 4 : 2); ++stages) {
-                        // three and four stages only for tiles the asynchronous pipeline can load
-                        if (stages >= 3 && find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n,
-                                                        v.mfma, v.amode, 1) < 0)
+                    for (int stages = (level >= 1 ? 1 : 2); stages <= (level >= 1 ? 6 : 2); ++stages) {
+                        // three and four stages only for tiles the asynchronous pipeline can load, five and six
+                        // only for tiles the patch kernel is compiled for
+                        if ((stages == 3 || stages == 4) &&
+                            find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode, 1) < 0)
+                            continue;
+                        if (stages >= 5 &&
+                            find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, 16, 2, 1) < 0 &&
+                            find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, 16, 2, 2) < 0)
                             continue;
                         tt_schedule r = make_record(cls, TT_SK_MFMA, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n,
                                                     v.mfma, splits[si], order, vfull, 8, stages);

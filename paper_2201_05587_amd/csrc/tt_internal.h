@@ -163,6 +163,9 @@ struct ContractArgs {
     int32_t C, H, W, R, S, stride_h, stride_w, pad_h, pad_w, Ho, Wo;
     int32_t run, runp;
     FastDiv div_hw, div_wo; // output pixel index -> (image, row, column)
+    // padded image geometry of the patch kernel: PW = W + 2 pad_w, PHW = (H + 2 pad_h) * PW
+    int32_t PW, PHW;
+    FastDiv div_phw, div_pw; // flat padded pixel index -> (image, padded row, padded column)
     uint32_t a_bytes, b_bytes; // sizes of the activation and filter tensors (bounds of the gathering loads)
     int32_t eff_vec_a, eff_vec_b, eff_vec_c, stages, unroll, act, has_bias, has_res, dtype;
 };
@@ -180,9 +183,12 @@ struct DwArgs {
 struct Variant {
     int32_t dtype, family, tile_m, tile_n, tile_k, wave_m, wave_n, mfma;
     int32_t amode; // conv family: bytes per gathered load (16 or the element size); 0 otherwise
-    int32_t pipe;  // 0: register-staged loads, 1 or 2 LDS stages; 1: asynchronous loads into a ring of 3 or 4
+    int32_t pipe;  // 0: register-staged loads, 1 or 2 LDS stages; 1: asynchronous loads into a ring of 3 or 4;
+                   // 2: 3x3 conv with the padded input patch in LDS and a filter ring of 3 or 4 (stages 5 or 6)
+    int32_t stride; // pipe 2: the convolution stride the kernel is compiled for; 0 otherwise
     int (*launch)(const ContractArgs &args, int grid, int lds_bytes, void *stream);
-    int (*stage_bytes)(); // LDS bytes of one pipeline stage, as the compiled kernel lays its tiles out
+    int (*stage_bytes)();        // pipes 0, 1: LDS bytes of one pipeline stage; pipe 2: pixels a patch buffer holds
+    int (*lds_bytes)(int stages); // LDS bytes for a plan's number of stages, as the compiled kernel lays LDS out
 };
 
 // Reduction elements one 16-byte operand fragment per lane feeds to the matrix cores: a block of MF rows
@@ -192,7 +198,8 @@ constexpr int k_granule(int dtype, int mfma) { return (dtype == TT_F32 ? 4 : 8) 
 // variant table (generated) and lookups
 extern const Variant kVariants[];
 extern const int kNumVariants;
-int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode, int pipe);
+int find_variant(int dtype, int family, int tm, int tn, int tk, int wm, int wn, int mf, int amode, int pipe,
+                 int stride = 0);
 int family_of(int cls, int trans_b);
 
 // launchers of the non-matrix-core kernels (simple_kernels.hip)

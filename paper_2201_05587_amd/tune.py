@@ -59,12 +59,28 @@ def fastest_distinct_tiles(dk: api.DeviceKernel, level: int, count: int, tiles=(
 
 
 def tune_donors(kernels: Sequence[wl.Kernel], seed_cfg: int, level: int = 1, log=None,
-                records_per_donor: int = 1) -> List[api.tt_schedule]:
+                records_per_donor: int = 1, checkpoint: Optional[str] = None,
+                resume: Optional[str] = None) -> List[api.tt_schedule]:
     """Native-tune every donor kernel; each contributes its optimum as one pool record (or, with
-    records_per_donor > 1, its fastest records of pairwise distinct workgroup tiles)."""
+    records_per_donor > 1, its fastest records of pairwise distinct workgroup tiles).
+
+    With `checkpoint` the pool so far is written to that file after every donor; `resume` names such a
+    file of an earlier run, whose donors are not tuned again (a long tuning job may be cut short).
+    """
+    import os
     import torch
     pool: List[api.tt_schedule] = []
+    done = 0
+    if resume and os.path.exists(resume) and records_per_donor == 1:
+        pool = load_pool(resume)
+        done = len(pool)
+        if log:
+            log(f"[pool] continuing after {done} donors found in {resume}")
     for i, k in enumerate(kernels):
+        if i < done:
+            continue
+        if checkpoint and records_per_donor == 1 and pool:
+            save_pool(checkpoint, pool, [kk.name for kk in kernels[:len(pool)]])
         dk = harness.device_kernel(k, wl.seed_for(seed_cfg, i), max_split=8)
         t0 = time.time()
         if records_per_donor > 1:

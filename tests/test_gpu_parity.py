@@ -466,3 +466,45 @@ def test_refinement_and_native_sweep_return_records_that_compute_the_operator(ap
     plan = api.tt_schedule_apply(nbest, k.cls, k.shape)
     assert plan.status == api.TT_OK and plan.variant_id >= 0
     P.check_kernel(k, [best, nbest], seed=5)
+
+
+# ---- 3x3 convolutions with the padded input patch in LDS (stages 5 and 6) ---------------------------
+PATCH_CASES = [
+    # (n, c, hw, k, stride), (tile_m, tile_n, tile_k, wave_m, wave_n), split_k, stages
+    ((2, 64, 28, 128, 1), (128, 128, 64, 64, 64), 1, 5),      # one channel slice, tiles cross image rows
+    ((3, 128, 14, 128, 1), (128, 128, 64, 64, 64), 1, 6),     # two slices, tiles cross images, ragged last tile (588 rows)
+    ((3, 128, 14, 128, 1), (128, 128, 64, 64, 64), 2, 5),     # the reduction split on the slice boundary
+    ((5, 256, 7, 192, 1), (128, 64, 64, 64, 32), 1, 5),       # 7 x 7 maps: a tile spans three images; ragged M (245) and N tiles
+    ((5, 256, 7, 192, 1), (64, 64, 64, 64, 32), 4, 6),        # four slices, one per split
+    ((1, 64, 224, 64, 1), (128, 64, 64, 64, 32), 1, 5),       # wide maps: the patch of a tile does not fit the buffer -> ring
+    ((2, 64, 56, 64, 1), (128, 64, 64, 64, 32), 1, 6),
+    ((1, 128, 20, 64, 1), (64, 64, 64, 64, 32), 1, 5),        # 20 x 20: rows that are no multiple of anything
+    ((2, 64, 28, 128, 2), (128, 128, 32, 64, 64), 1, 5),      # stride 2: 28 -> 14
+    ((4, 96, 14, 128, 2), (64, 128, 32, 64, 64), 3, 6),       # stride 2 on 14 -> 7, three slices of 32, one per split
+    ((2, 64, 27, 64, 2), (64, 64, 32, 64, 32), 1, 5),         # odd input size under stride 2
+    ((2, 128, 12, 256, 1), (64, 128, 64, 32, 64), 1, 5),      # wave tile split along the columns
+    ((2, 64, 30, 128, 1), (256, 64, 64, 64, 64), 1, 5),
+    ((2, 64, 24, 256, 1), (256, 128, 64, 64, 64), 1, 5),      # sixteen waves
+]
+
+
+@pytest.mark.parametrize("case", PATCH_CASES)
+@pytest.mark.parametrize("cls", [wl.CLS_CONV2D_BIAS_RELU, wl.CLS_CONV2D_BIAS_ADD_RELU])
+def test_conv3x3_with_the_input_patch_in_lds(api, P, case, cls):
+    (n, c, hw, kk, st), (tm, tn, tk, wm, wn), split, stages = case
+    k = conv_kernel(cls, n, c, hw, kk, 3, st, dtype=wl.BF16)
+    rec = mfma(api, cls, tm, tn, tk, wm, wn, 32, split_k=split, order=(stages + split) % 6, stages=stages)
+    plan = api.tt_schedule_apply(rec, k.cls, k.shape)
+    assert plan.status == api.TT_OK and plan.variant_id >= 0, (plan.status, plan.reason)
+    P.check_kernel(k, [rec], seed=505 + stages)
+
+
+def test_patch_kernel_is_the_one_that_runs_where_it_applies(api):
+    """The cases above exercise the patch kernel (pipeline 2), except the one built to overflow its buffer."""
+    ran = []
+    for (n, c, hw, kk, st), (tm, tn, tk, wm, wn), split, stages in PATCH_CASES:
+        k = conv_kernel(wl.CLS_CONV2D_BIAS_RELU, n, c, hw, kk, 3, st, dtype=wl.BF16)
+        rec = mfma(api, k.cls, tm, tn, tk, wm, wn, 32, split_k=split, stages=stages)
+        plan = api.tt_schedule_apply(rec, k.cls, k.shape)
+        ran.append(api.tt_variant_info(plan.variant_id)[9])
+    assert ran.count(2) == len(PATCH_CASES) - 1 and ran[5] == 1

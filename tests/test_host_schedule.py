@@ -92,7 +92,7 @@ def random_record(rng, cls):
     mf = rng.choice([16, 32])
     return S.record(cls, S.SK_MFMA, tm, tn, rng.choice([16, 32, 64, 128]), rng.choice([16, 32, 64, 128]),
                     rng.choice([16, 32, 64, 128]), mf, rng.choice([1, 1, 2, 3, 4, 8, 16, 64]), rng.randrange(6),
-                    rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 512]), rng.choice([1, 2, 3, 4]))
+                    rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 512]), rng.choice([1, 2, 3, 4, 5, 6]))
 
 
 def test_apply_matches_oracle_bit_for_bit_on_random_records():
@@ -135,13 +135,21 @@ def check_library_fields(cplan, rec, k):
             v = getattr(cplan, f)
             assert v == S.pow2_dividing(min(rec["vec"], widest), extent), (f, v, rec["vec"], extent)
         assert 1 <= cplan.eff_unroll <= rec["unroll"]
-        assert cplan.stages == rec["stages"] or (rec["stages"] >= 3 and cplan.stages == 2)
+        # reformulation chain of the cache-buffer knob: patch + ring (5, 6) -> ring (3, 4) -> two register stages
+        assert cplan.stages in {rec["stages"]} | ({rec["stages"] - 2, 2} if rec["stages"] >= 5 else set()) | \
+            ({2} if rec["stages"] >= 3 else set())
         if cplan.variant_id >= 0:
             v = dict(zip(api.VARIANT_INFO, api.tt_variant_info(cplan.variant_id)))
             assert (v["dtype"], v["tile_m"], v["tile_n"], v["tile_k"], v["wave_m"], v["wave_n"], v["mfma"]) == \
                 (s.dtype, rec["tile_m"], rec["tile_n"], rec["tile_k"], rec["wave_m"], rec["wave_n"], rec["mfma"])
-            assert v["pipe"] == (1 if cplan.stages >= 3 else 0)
-            assert cplan.lds_bytes == cplan.stages * v["stage_bytes"] <= 160 * 1024
+            assert v["pipe"] == (2 if cplan.stages >= 5 else 1 if cplan.stages >= 3 else 0)
+            if v["pipe"] < 2:
+                assert cplan.lds_bytes == cplan.stages * v["stage_bytes"] <= 160 * 1024
+            else:
+                # two patch buffers of the exported pixel capacity and a ring of stages - 2 filter tiles
+                assert 160 * 1024 >= cplan.lds_bytes >= 2 * v["stage_bytes"] * rec["tile_k"] * 2 + \
+                    (cplan.stages - 2) * rec["tile_n"] * rec["tile_k"] * 2
+                assert s.c % rec["tile_k"] == 0 and cplan.k_iters % 9 == 0 and (s.r, s.s) == (3, 3)
             assert rec["tile_k"] % v["k_granule"] == 0
             assert cplan.eff_unroll == min(rec["unroll"], rec["tile_k"] // v["k_granule"])
             # a stage holds at least the two operand tiles
@@ -231,17 +239,19 @@ def test_resource_rejections_come_from_the_compiled_kernels():
     p = api.tt_schedule_apply(api.make_schedule(bsh.cls, tile_k=16, mfma=16, vec=8), bsh.cls, bsh.shape)
     assert (p.status, p.reason) == (api.TT_ERR_INVALID_SCHEDULE, 7)
     assert api.tt_schedule_apply(api.make_schedule(bsh.cls, tile_k=16, mfma=32, vec=8), bsh.cls, bsh.shape).status == api.TT_OK
-    # the largest compiled tile does not fit twice: two stages are refused, one stage is a plan
-    big = max((v for v in vs if v["dtype"] == wl.BF16 and v["family"] == 1 and v["pipe"] == 0), key=lambda v: v["stage_bytes"])
-    assert 2 * big["stage_bytes"] > 160 * 1024 >= big["stage_bytes"]
+    # a ring tile that fits three times but not four: four stages are refused, three are a plan
+    fits3 = [v for v in vs if v["dtype"] == wl.BF16 and v["family"] == 1 and v["pipe"] == 1
+             and 3 * v["stage_bytes"] <= 160 * 1024 < 4 * v["stage_bytes"]]
+    assert fits3
+    big = fits3[0]
     wide = wl.Kernel(wl.CLS_DENSE_ADD, wl.GemmShape(1, 4096, 4096, 4096, 1, wl.BF16))
     rec = {f: big[f] for f in ("tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfma")}
-    two = api.tt_schedule_apply(api.make_schedule(wide.cls, vec=8, stages=2, **rec), wide.cls, wide.shape)
-    one = api.tt_schedule_apply(api.make_schedule(wide.cls, vec=8, stages=1, **rec), wide.cls, wide.shape)
+    two = api.tt_schedule_apply(api.make_schedule(wide.cls, vec=8, stages=4, **rec), wide.cls, wide.shape)
+    one = api.tt_schedule_apply(api.make_schedule(wide.cls, vec=8, stages=3, **rec), wide.cls, wide.shape)
     assert (two.status, two.reason) == (api.TT_ERR_INVALID_SCHEDULE, 6)
-    assert one.status == api.TT_OK and one.lds_bytes == big["stage_bytes"]
+    assert one.status == api.TT_OK and one.lds_bytes == 3 * big["stage_bytes"]
     # the method still accepts both: the oracle knows nothing of LDS
-    orec = S.record(wide.cls, vec=8, stages=2, **rec)
+    orec = S.record(wide.cls, vec=8, stages=4, **rec)
     assert S.apply(orec, wide.cls, oshape(wide))["status"] == S.OK
 
 
@@ -263,8 +273,44 @@ def test_ring_stages_are_reformulated_where_no_ring_kernel_applies():
     bm = wl.CLS_BATCH_MATMUL
     assert api.tt_schedule_apply(api.make_schedule(bm, stages=3, **rec), bm, wl.GemmShape(4, 128, 128, 64, 0, bf)).stages == 2
     assert api.tt_schedule_apply(api.make_schedule(bm, stages=3, **rec), bm, wl.GemmShape(4, 128, 128, 64, 1, bf)).stages == 3
-    # five stages is not a record
-    assert api.tt_schedule_apply(api.make_schedule(E, stages=5, **rec), E, conv).status == api.TT_ERR_BAD_ARG
+    # seven stages is not a record
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=7, **rec), E, conv).status == api.TT_ERR_BAD_ARG
+
+
+def test_patch_stages_apply_to_3x3_bf16_convolutions_and_are_reformulated_elsewhere():
+    bf = wl.BF16
+    E = wl.CLS_CONV2D_BIAS_RELU
+    rec = dict(tile_m=128, tile_n=128, tile_k=64, wave_m=64, wave_n=64, mfma=32, vec=8, unroll=8)
+    s3 = wl.ConvShape(32, 256, 14, 14, 256, 3, 3, 1, 1, 1, 1, bf)
+    p = api.tt_schedule_apply(api.make_schedule(E, stages=5, **rec), E, s3)
+    info = dict(zip(api.VARIANT_INFO, api.tt_variant_info(p.variant_id)))
+    assert (p.status, p.stages, info["pipe"]) == (api.TT_OK, 5, 2) and p.block == 256  # wave positions; two waves each
+    # 128 consecutive output pixels of 14 x 14 maps: at most 10 rows of 16 padded pixels plus the two-row,
+    # two-column halo, and one more row pair where the run crosses into the next image
+    assert 200 <= info["stage_bytes"]
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=6, **rec), E, s3).stages == 6
+    # a split of the reduction on a channel-slice boundary keeps the patch kernel (4 slices: 2 + 2) ...
+    p = api.tt_schedule_apply(api.make_schedule(E, stages=5, split_k=2, **rec), E, s3)
+    assert (p.stages, p.k_iters, p.eff_split_k) == (5, 18, 2)
+    # ... one that cuts through a slice's nine taps falls back to the ring (36 K tiles in 3 splits of 12)
+    p = api.tt_schedule_apply(api.make_schedule(E, stages=5, split_k=3, **rec), E, s3)
+    assert (p.stages, p.k_iters) == (3, 12) and api.tt_variant_info(p.variant_id)[9] == 1
+    # 1x1 filters, fp32, 16-blocks, 96 channels (64 does not divide them): the ring, or two stages where there is none
+    pw = wl.ConvShape(32, 256, 14, 14, 256, 1, 1, 1, 1, 0, 0, bf)
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=6, **rec), E, pw).stages == 4
+    f32 = wl.ConvShape(4, 256, 14, 14, 256, 3, 3, 1, 1, 1, 1, wl.F32)
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=5, **dict(rec, tile_k=32, vec=4)), E, f32).stages in (2, 3)
+    c96 = wl.ConvShape(32, 96, 14, 14, 256, 3, 3, 1, 1, 1, 1, bf)
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=5, **rec), E, c96).stages == 3
+    # a patch that does not fit the kernel's buffer: 128 output pixels of a 112-wide map under stride 2
+    wide = wl.ConvShape(2, 64, 224, 224, 128, 3, 3, 2, 2, 1, 1, bf)
+    p = api.tt_schedule_apply(api.make_schedule(E, stages=5, **dict(rec, tile_k=32)), E, wide)
+    assert p.status == api.TT_OK and p.stages == 3
+    # the method's fields do not depend on the knob
+    for st in (2, 4, 6):
+        o = S.apply(S.record(E, stages=st, **rec), E, oshape(wl.Kernel(E, s3)))
+        c = api.tt_schedule_apply(api.make_schedule(E, stages=st, **rec), E, s3)
+        assert plan_equal(c, o, S.record(E, stages=st, **rec))
 
 
 def test_division_by_multiplication_is_exact():
