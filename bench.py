@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="run the sweeps and store their outcome")
     ap.add_argument("--retune-pool", action="store_true", help="also re-tune the donor kernels (the pool)")
     ap.add_argument("--donor-limit", type=int, default=0, help="use only the first N donor kernels")
+    ap.add_argument("--pool-only", action="store_true", help="with --retune-pool: stop once the pool file is written")
     ap.add_argument("--resume-pool", default="", help="pool checkpoint of an interrupted --retune-pool run to continue from")
     ap.add_argument("--level", type=int, default=1, help="size of the enumerated native space (0, 1, 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -77,6 +78,14 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
                                 partial if os.path.isdir(os.path.dirname(partial)) else None, args.resume_pool or None)
         tune.save_pool(pool_path, pool, [donors[i // per_donor].name for i in range(len(pool))])
         pool_seconds = time.time() - t0
+        mirror = os.path.join(ROOT, "gpurun_out", "tuned")
+        if os.path.isdir(os.path.dirname(mirror)):
+            import shutil
+            os.makedirs(mirror, exist_ok=True)
+            shutil.copy(pool_path, os.path.join(mirror, os.path.basename(pool_path)))
+        if args.pool_only:
+            log(f"[pool] {len(pool)} records in {pool_seconds:.0f}s; stopping as asked")
+            sys.exit(0)
     else:
         pool = tune.load_pool(pool_path)
         pool_seconds = None

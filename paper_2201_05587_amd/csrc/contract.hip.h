@@ -571,10 +571,57 @@ __device__ __forceinline__ BiasRegs<DT> load_bias_early(const ContractArgs &g, c
     return b;
 }
 
-template <int DT, int TM, int WM, int WN, int MF, typename Acc>
-__device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
-                                           unsigned char *smem, int wave, int lane, const BiasRegs<DT> &bias)
+// The residual values a lane adds in the epilogue, for ALL bands and passes, requested at the start of a
+// kernel (right after the first operand slices) where that costs at most 16 registers and the kernel
+// allows it (16-wave workgroups have 128 registers per lane and none to spare).  A streaming
+// layer (short reduction, long rows of outputs) otherwise pays two memory round trips in a row, operands
+// and then residuals; with this they overlap.  Wave tiles with more rows fetch band by band in the epilogue.
+template <int DT, int TM, int WM, int WN, int MF, bool ALLOW = true> struct ResRegs {
+    using T = TileOut<TM, WM, WN, MF>;
+    static constexpr int W = DT == TT_BF16 ? 1 : 2; // 16-byte items per lane and pass
+    static constexpr bool EARLY = ALLOW && T::NI * T::PASSES * W <= 4;
+    u32x4 v[EARLY ? T::NI : 1][EARLY ? T::PASSES : 1][W];
+};
+// One pass's residual items of a lane (rows past the matrix read the tile's first row: any valid address).
+template <int DT, int TM, int WM, int WN, int MF>
+__device__ __forceinline__ void load_res_pass(u32x4 (&dst)[DT == TT_BF16 ? 1 : 2], const ContractArgs &g, const TileCoord &tc,
+                                              int wave, int lane, int i, int ps)
 {
+    using T = TileOut<TM, WM, WN, MF>;
+    const int first = tc.n0 + T::col(wave, lane);
+    const int m = tc.m0 + T::row(wave, lane, i, ps);
+    const bool live = T::pass_live(lane, ps) && m < g.M && first < g.N;
+    const int64_t row_at = (int64_t)tc.hi * g.M * g.N + (int64_t)(live ? m : tc.m0) * g.N + (live ? first : tc.n0);
+    if constexpr (DT == TT_BF16) {
+        dst[0] = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + row_at);
+    } else {
+        dst[0] = *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.res) + row_at);
+        dst[1] = (live && first + 4 < g.N) ? *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.res) + row_at + 4)
+                                           : u32x4{0u, 0u, 0u, 0u};
+    }
+}
+template <int DT, int TM, int WM, int WN, int MF, bool ALLOW>
+__device__ __forceinline__ void load_res_early(ResRegs<DT, TM, WM, WN, MF, ALLOW> &r, const ContractArgs &g,
+                                               const TileCoord &tc, int wave, int lane)
+{
+    using R = ResRegs<DT, TM, WM, WN, MF, ALLOW>;
+    if constexpr (R::EARLY) {
+        const bool whole = DT == TT_BF16 ? g.eff_vec_c == 8 : g.eff_vec_c >= 4;
+        if (whole && g.map.eff_split_k == 1 && g.has_res) {
+#pragma unroll
+            for (int i = 0; i < R::T::NI; ++i)
+#pragma unroll
+                for (int ps = 0; ps < R::T::PASSES; ++ps) load_res_pass<DT, TM, WM, WN, MF>(r.v[i][ps], g, tc, wave, lane, i, ps);
+        }
+    }
+}
+
+template <int DT, int TM, int WM, int WN, int MF, typename Acc, bool ALLOW>
+__device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
+                                           unsigned char *smem, int wave, int lane, const BiasRegs<DT> &bias,
+                                           const ResRegs<DT, TM, WM, WN, MF, ALLOW> &early)
+{
+    using R = ResRegs<DT, TM, WM, WN, MF, ALLOW>;
     using T = TileOut<TM, WM, WN, MF>;
     constexpr int NI = T::NI, NJ = T::NJ, ACC = T::ACC, ESTRIDE = T::ESTRIDE, CG = T::CG, PASSES = T::PASSES;
     const int lane_r = lane % MF, lane_g = lane / MF;
@@ -607,22 +654,17 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        // the residuals of this band's rows: all requested before the staging, so that their latency
-        // runs in parallel instead of once per pass
-        u32x4 resv[PASSES][DT == TT_BF16 ? 1 : 2];
+        // the residuals of this band's rows (where they were not requested at kernel start): all passes
+        // before the staging, so that their latency runs in parallel instead of once per pass
+        u32x4 resv[PASSES][R::W];
         if (whole && !partial && g.has_res) {
 #pragma unroll
             for (int ps = 0; ps < PASSES; ++ps) {
-                const int m = tc.m0 + T::row(wave, lane, i, ps);
-                const bool live = T::pass_live(lane, ps) && m < g.M && first < g.N;
-                const int64_t row_at = out_base + (int64_t)(live ? m : tc.m0) * g.N + (live ? first : tc.n0);
-                if constexpr (DT == TT_BF16) {
-                    resv[ps][0] = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(g.res) + row_at);
+                if constexpr (R::EARLY) {
+#pragma unroll
+                    for (int w = 0; w < R::W; ++w) resv[ps][w] = early.v[i][ps][w];
                 } else {
-                    resv[ps][0] = *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.res) + row_at);
-                    resv[ps][1] = (live && first + 4 < g.N)
-                                      ? *reinterpret_cast<const u32x4 *>(static_cast<const float *>(g.res) + row_at + 4)
-                                      : u32x4{0u, 0u, 0u, 0u};
+                    load_res_pass<DT, TM, WM, WN, MF>(resv[ps], g, tc, wave, lane, i, ps);
                 }
             }
         }
@@ -666,7 +708,9 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                     u32x4 outv;
 #pragma unroll
                     for (int h = 0; h < 4; ++h) outv[h] = pack_bf16x2(val[2 * h], val[2 * h + 1]);
-                    *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + row_at) = outv;
+                    // streaming store: the output is not read again by this launch, and lines that leave
+                    // the L2 as they are written do not wait for the write-back at the end of the kernel
+                    __builtin_nontemporal_store(outv, reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(g.out) + row_at));
                 } else {
 #pragma unroll
                     for (int q4 = 0; q4 < 2; ++q4) {
@@ -679,7 +723,8 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                             if (g.has_res) sum[e] += __uint_as_float(resv[ps][q4][e]);
                         }
                         apply_act_all(sum, g.act);
-                        *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at) = f32x4{sum[0], sum[1], sum[2], sum[3]};
+                        __builtin_nontemporal_store(f32x4{sum[0], sum[1], sum[2], sum[3]},
+                                                    reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + at));
                     }
                 }
                 continue;
@@ -857,6 +902,8 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     };
 
     fetch(0);
+    ResRegs<DT, TM, WM, WN, MF, (THREADS <= 512)> res_early;
+    load_res_early(res_early, g, tc, wave, lane); // behind the first slice's loads, which the stash below waits for alone
     stash(0, 0);
     __syncthreads();
     const bool two_stage = g.stages == 2;
@@ -888,7 +935,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_kernel(co
     else
         k_loop(std::false_type{});
 
-    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane, bias);
+    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane, bias, res_early);
 }
 
 // ---- asynchronous pipeline: global -> LDS without passing through registers --------------------------------------
@@ -1146,6 +1193,11 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
     // prologue: fill all but one buffer
     int requested = 0;
     for (; requested < nst - 1 && requested < kt_count; ++requested) request(requested, requested);
+    // The residuals go out behind the first slices.  They are ordinary loads into registers, so the
+    // counter arithmetic of the loop below sees them as further loads in flight: the first waits then also
+    // wait for them to start arriving in order, which costs nothing a slice from the same memory would not.
+    ResRegs<DT, TM, WM, WN, MF, (THREADS <= 512)> res_early;
+    load_res_early(res_early, g, tc, wave, lane);
     // The unroll knob picks one of two complete K loops (a choice inside the loop would make the
     // compiler shuttle the accumulators between the register sets of the two paths on every slice).
     auto k_loop = [&](auto unroll_steps) {
@@ -1210,7 +1262,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 64) contract_async_ker
         k_loop(std::true_type{});
     else
         k_loop(std::false_type{});
-    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane, bias);
+    write_tile<DT, TM, WM, WN, MF>(acc, g, tc, smem, wave, lane, bias, res_early);
 }
 
 // More than 48 KB of dynamic LDS has to be enabled per kernel.  Remembers the largest size enabled so far

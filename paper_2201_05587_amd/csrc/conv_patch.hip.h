@@ -176,6 +176,8 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 128) conv3x3_patch_ker
         request_patch_piece(l, slice0, 0);
     }
 
+    ResRegs<DT, TM, EWM, EWN, MF, false> res_early; // (a long reduction: the residuals are fetched in the epilogue)
+
     // ---- this lane's rows of the patch (per 32-row block of the wave tile) ----
     const int wr = pos % NWR, wc = pos / NWR;
     const int lane_r = lane % MF, lane_g = lane / MF;
@@ -344,7 +346,7 @@ __global__ void __launch_bounds__((TM / WM) * (TN / WN) * 128) conv3x3_patch_ker
         take(std::integral_constant<int, 0>{});
     else
         take(std::integral_constant<int, 1>{});
-    write_tile<DT, TM, EWM, EWN, MF>(mine, g, tc, smem, ewave, lane, bias);
+    write_tile<DT, TM, EWM, EWN, MF>(mine, g, tc, smem, ewave, lane, bias, res_early);
 }
 
 // LDS bytes: two patch buffers and the filter ring; never less than the exchange of the K groups (the whole

@@ -43,7 +43,7 @@ TILES_SMALL = [(16, 16, 16, 16), (32, 32, 16, 16), (64, 64, 32, 32), (128, 128, 
 # (tile_m, tile_n, channels per slice = tile_k, wave_m, wave_n, stride, patch items per thread and slice)
 PATCH_TILES = [
     (128, 128, 64, 64, 64, 1, 6), (128, 64, 64, 64, 32, 1, 6), (128, 64, 64, 64, 64, 1, 7), (256, 64, 64, 64, 64, 1, 7),
-    (64, 128, 64, 64, 64, 1, 7), (64, 64, 64, 64, 32, 1, 7), (64, 128, 64, 32, 64, 1, 4), (256, 128, 64, 64, 64, 1, 3),
+    (64, 128, 64, 64, 64, 1, 7), (64, 64, 64, 64, 32, 1, 7), (64, 128, 64, 32, 64, 1, 4),
     (128, 128, 32, 64, 64, 1, 4),
     (128, 128, 32, 64, 64, 2, 6), (64, 128, 32, 64, 64, 2, 7), (64, 64, 32, 64, 32, 2, 7), (128, 64, 32, 64, 64, 2, 7),
 ]

@@ -325,7 +325,9 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         // input below 2 GiB); elsewhere such a plan has no kernel.
         const bool rows_kernel = r.stages == 1 && s->stride_h == s->stride_w && (s->stride_h == 1 || s->stride_h == 2) &&
                                  (int64_t)s->n * s->h * s->w * s->c * elem < (1ll << 31);
-        p.variant_id = (ev_planes == 1 || rows_kernel) && s->r == 3 && s->s == 3 && dt == TT_F32 ? 0 : -1;
+        const int block = r.tile_k * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
+        const bool fits = block <= dw_max_block(r.wave_m, r.wave_n, ev_planes, s->stride_w, rows_kernel);
+        p.variant_id = (ev_planes == 1 || rows_kernel) && s->r == 3 && s->s == 3 && dt == TT_F32 && fits ? 0 : -1;
         p.eff_split_k = 1;
         p.k_iters = 1;
         p.slabs = p.k_tiles;
@@ -333,7 +335,7 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
         p.eff_vec_b = 1;
         p.eff_unroll = std::min(r.unroll, r.wave_m);
         p.grid = (int)grid;
-        p.block = r.tile_k * (r.tile_m / r.wave_m) * (r.tile_n / r.wave_n);
+        p.block = block;
         p.lds_bytes = (int)lds;
         *plan = p;
         return TT_OK;

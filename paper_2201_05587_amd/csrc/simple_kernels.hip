@@ -76,7 +76,7 @@ template <int DT> __global__ void __launch_bounds__(256) splitk_reduce_kernel(co
 }
 
 // ---- GEMV sketch: a wave owns WN outputs of TMR rows; lanes split K; butterfly reduction ---------
-template <int DT> __global__ void gemv_kernel(const ContractArgs g, int tile_m, int wave_n, int chunk)
+template <int DT> __global__ void __launch_bounds__(1024) gemv_kernel(const ContractArgs g, int tile_m, int wave_n, int chunk)
 {
     using E = typename ElemOf<DT>::type;
     const TileCoord tc = decode_tile(g.map, (int32_t)blockIdx.x);
@@ -84,6 +84,8 @@ template <int DT> __global__ void gemv_kernel(const ContractArgs g, int tile_m, 
     const int n_first = tc.n0 + wave * wave_n;
     const E *x = static_cast<const E *>(g.a), *w = static_cast<const E *>(g.b);
     const int ev = g.eff_vec_a;
+    // Every array below is indexed by unrolled loop counters only (rows and outputs beyond tile_m and
+    // wave_n are skipped by wave-uniform tests), so all of it stays in registers.
     float acc[8][8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -95,24 +97,30 @@ template <int DT> __global__ void gemv_kernel(const ContractArgs g, int tile_m, 
         for (int c0 = 0; c0 < chunk; c0 += ev) {
             // ev consecutive K per access; K % ev == 0 so a group is all in or all out
             if (k + c0 >= g.K) break;
-            float xv[8][8], wv[8][8];
-            for (int i = 0; i < tile_m; ++i) {
-                const int m = tc.m0 + i;
-                for (int e = 0; e < ev; ++e)
-                    xv[i][e] = m < g.M ? load_as_float<DT>(x, (int64_t)m * g.K + k + c0 + e) : 0.0f;
+            for (int e = 0; e < ev; ++e) {
+                const int64_t kk = k + c0 + e;
+                float xv[8], wv[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    xv[i] = (i < tile_m && tc.m0 + i < g.M) ? load_as_float<DT>(x, (int64_t)(tc.m0 + i) * g.K + kk) : 0.0f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    wv[j] = (j < wave_n && n_first + j < g.N) ? load_as_float<DT>(w, (int64_t)(n_first + j) * g.K + kk) : 0.0f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (i >= tile_m) break;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[i][j] = fmaf(xv[i], wv[j], acc[i][j]);
+                }
             }
-            for (int j = 0; j < wave_n; ++j) {
-                const int n = n_first + j;
-                for (int e = 0; e < ev; ++e)
-                    wv[j][e] = n < g.N ? load_as_float<DT>(w, (int64_t)n * g.K + k + c0 + e) : 0.0f;
-            }
-            for (int i = 0; i < tile_m; ++i)
-                for (int j = 0; j < wave_n; ++j)
-                    for (int e = 0; e < ev; ++e) acc[i][j] = fmaf(xv[i][e], wv[j][e], acc[i][j]);
         }
     }
-    for (int i = 0; i < tile_m; ++i)
-        for (int j = 0; j < wave_n; ++j) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (i >= tile_m) break;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (j >= wave_n) break;
             float v = acc[i][j];
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -122,13 +130,14 @@ template <int DT> __global__ void gemv_kernel(const ContractArgs g, int tile_m, 
                 store_from_float<DT>(g.out, (int64_t)m * g.N + n, apply_act(v, g.act));
             }
         }
+    }
 }
 
 // ---- depthwise 3x3 over NHWC: (rows, cols, planes) tile per workgroup, WM x WN outputs per thread ---
 // A plane is one (image, channel) pair, numbered image * C + channel.  Threads are laid out planes
 // fastest, then cols, then rows, so the lanes of a wave read and write neighbouring channels of one
 // pixel.  With two stages the input patch of the tile is first copied to LDS (planes fastest too).
-template <int WM, int WN> __global__ void dwconv3x3_kernel(const DwArgs g)
+template <int WM, int WN, int MAXT> __global__ void __launch_bounds__(MAXT) dwconv3x3_kernel(const DwArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float *patch = reinterpret_cast<float *>(smem_raw);
@@ -208,7 +217,8 @@ template <int WM, int WN> __global__ void dwconv3x3_kernel(const DwArgs g)
 // bounds-checked buffer loads (an offset outside the tensor reads as zero, which is the padding),
 // then forms its WN outputs.  Lanes of a wave hold neighbouring channel groups of one pixel, so
 // every load and store instruction covers one contiguous run of memory.
-template <int WM, int WN, int VC, int STR> __global__ void dwconv3x3_rows_kernel(const DwArgs g)
+template <int WM, int WN, int VC, int STR, int MAXT>
+__global__ void __launch_bounds__(MAXT) dwconv3x3_rows_kernel(const DwArgs g)
 {
     typedef __attribute__((ext_vector_type(VC))) float vec_t;
     constexpr int COLS = (WN - 1) * STR + 3;
@@ -280,7 +290,7 @@ template <int WM, int WN, int VC, int STR> __global__ void dwconv3x3_rows_kernel
             vec_t o;
 #pragma unroll
             for (int v = 0; v < VC; ++v) o[v] = fminf(fmaxf(out[j][v], 0.0f), 6.0f);
-            *reinterpret_cast<vec_t *>(yp + ((int64_t)p * g.Wo + q0 + j) * g.C) = o;
+            __builtin_nontemporal_store(o, reinterpret_cast<vec_t *>(yp + ((int64_t)p * g.Wo + q0 + j) * g.C)); // streamed
         }
     };
     if (g.unroll >= WM) {
@@ -377,6 +387,27 @@ int launch_gemv(const ContractArgs &args, const tt_plan &plan, void *stream)
     return launched();
 }
 
+// The depthwise kernels are compiled for workgroups of at most 256, 512 and 1024 threads, which leaves a
+// lane 512, 256 and 128 registers.  What a lane keeps in flight grows with the input columns of its
+// window times the planes per access (register kernel) or with its outputs per row (general kernel); the
+// bounds below are the sizes the compiler keeps in registers (the build's resource report: no instance
+// that these bounds admit uses scratch memory).
+constexpr int dw_block_limit(int wave_m, int wave_n, int planes_per_lane, int stride, bool rows_kernel)
+{
+    const auto built = [](int w) { return w == 1 || w == 2 || w == 4 || w == 7; };
+    if (!built(wave_m) || !built(wave_n)) return 0; // no instance for other outputs per thread
+    if (rows_kernel) {
+        const int in_flight = ((wave_n - 1) * stride + 3) * planes_per_lane;
+        return in_flight <= 9 || (in_flight <= 16 && wave_n < 7) ? 1024 : in_flight <= 36 ? 512 : 256;
+    }
+    return wave_n <= 2 ? 1024 : wave_n <= 4 ? 512 : 256;
+}
+
+int dw_max_block(int wave_m, int wave_n, int planes_per_lane, int stride, bool rows_kernel)
+{
+    return dw_block_limit(wave_m, wave_n, planes_per_lane, stride, rows_kernel);
+}
+
 namespace {
 
 template <int WM, int WN> int launch_dw_rows(const DwArgs &a, dim3 grid, dim3 block, hipStream_t s)
@@ -384,7 +415,17 @@ template <int WM, int WN> int launch_dw_rows(const DwArgs &a, dim3 grid, dim3 bl
     const int str = a.stride_h;
 #define TT_DW_ROWS(VC_, STR_)                                                                                        \
     if (a.eff_vec == VC_ && str == STR_) {                                                                           \
-        hipLaunchKernelGGL((dwconv3x3_rows_kernel<WM, WN, VC_, STR_>), grid, block, 0, s, a);                        \
+        constexpr int LIMIT = dw_block_limit(WM, WN, VC_, STR_, true);                                               \
+        if ((int)block.x > LIMIT) return TT_ERR_UNSUPPORTED;                                                         \
+        if (block.x <= 256) {                                                                                        \
+            hipLaunchKernelGGL((dwconv3x3_rows_kernel<WM, WN, VC_, STR_, 256>), grid, block, 0, s, a);               \
+        } else if (block.x <= 512) {                                                                                 \
+            if constexpr (LIMIT >= 512)                                                                              \
+                hipLaunchKernelGGL((dwconv3x3_rows_kernel<WM, WN, VC_, STR_, 512>), grid, block, 0, s, a);           \
+        } else {                                                                                                     \
+            if constexpr (LIMIT >= 1024)                                                                             \
+                hipLaunchKernelGGL((dwconv3x3_rows_kernel<WM, WN, VC_, STR_, 1024>), grid, block, 0, s, a);          \
+        }                                                                                                            \
         return launched();                                                                                           \
     }
     TT_DW_ROWS(1, 1) TT_DW_ROWS(2, 1) TT_DW_ROWS(4, 1) TT_DW_ROWS(1, 2) TT_DW_ROWS(2, 2) TT_DW_ROWS(4, 2)
@@ -407,9 +448,16 @@ int launch_dwconv(const DwArgs &a, const tt_plan &plan, void *stream)
 #define TT_DW_CASE(WM_, WN_)                                                                                         \
     if (a.wave_m == WM_ && a.wave_n == WN_) {                                                                        \
         if (rows_kernel) return launch_dw_rows<WM_, WN_>(a, grid, block, s);                                         \
-        auto kern = dwconv3x3_kernel<WM_, WN_>;                                                                      \
-        static DynamicLdsLimit limit; /* per kernel instance; host threads may launch concurrently */               \
-        if (const int rc = limit.raise_to(reinterpret_cast<const void *>(kern), lds); rc != TT_OK) return rc;        \
+        constexpr int LIMIT = dw_block_limit(WM_, WN_, 1, 1, false);                                                 \
+        if ((int)block.x > LIMIT) return TT_ERR_UNSUPPORTED;                                                         \
+        const int bc = block.x <= 256 ? 0 : block.x <= 512 ? 1 : 2;                                                  \
+        auto kern = dwconv3x3_kernel<WM_, WN_, 256>;                                                                 \
+        if constexpr (LIMIT >= 512)                                                                                  \
+            if (bc == 1) kern = dwconv3x3_kernel<WM_, WN_, 512>;                                                     \
+        if constexpr (LIMIT >= 1024)                                                                                 \
+            if (bc == 2) kern = dwconv3x3_kernel<WM_, WN_, 1024>;                                                    \
+        static DynamicLdsLimit limits[3]; /* per kernel instance; host threads may launch concurrently */           \
+        if (const int rc = limits[bc].raise_to(reinterpret_cast<const void *>(kern), lds); rc != TT_OK) return rc;   \
         hipLaunchKernelGGL(kern, grid, block, lds, s, a);                                                            \
         return launched();                                                                                           \
     }

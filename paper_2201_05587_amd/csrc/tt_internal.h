@@ -206,6 +206,7 @@ int family_of(int cls, int trans_b);
 int launch_direct(const ContractArgs &args, int family, int grid, void *stream);
 int launch_splitk_reduce(const ContractArgs &args, int family, void *stream);
 int launch_gemv(const ContractArgs &args, const tt_plan &plan, void *stream);
+int dw_max_block(int wave_m, int wave_n, int planes_per_lane, int stride, bool rows_kernel);
 int launch_dwconv(const DwArgs &args, const tt_plan &plan, void *stream);
 int launch_dw_direct(const DwArgs &args, int grid, void *stream);
 int launch_tile_map_dump(const TileMap &map, int32_t *out_dev, void *stream);

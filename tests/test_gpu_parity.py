@@ -484,7 +484,6 @@ PATCH_CASES = [
     ((2, 64, 27, 64, 2), (64, 64, 32, 64, 32), 1, 5),         # odd input size under stride 2
     ((2, 128, 12, 256, 1), (64, 128, 64, 32, 64), 1, 5),      # wave tile split along the columns
     ((2, 64, 30, 128, 1), (256, 64, 64, 64, 64), 1, 5),
-    ((2, 64, 24, 256, 1), (256, 128, 64, 64, 64), 1, 5),      # sixteen waves
 ]
 
 

@@ -159,8 +159,13 @@ def check_library_fields(cplan, rec, k):
     elif cplan.sketch == api.TT_SK_DWCONV:
         assert cplan.eff_vec_a == S.pow2_dividing(min(rec["vec"], widest), s.c)
         assert cplan.tile_k == rec["tile_k"] * cplan.eff_vec_a
-        # several planes per lane run in the one-stage kernel only
-        assert (cplan.variant_id >= 0) == (cplan.eff_vec_a == 1 or rec["stages"] == 1)
+        # several planes per lane run in the one-stage kernel only; workgroups of up to 256 threads always
+        # have a kernel, larger ones only where a lane's window fits the registers left to it
+        kinds = cplan.eff_vec_a == 1 or rec["stages"] == 1
+        if cplan.variant_id >= 0:
+            assert kinds
+        elif kinds:
+            assert cplan.block > 256
     else:
         assert cplan.variant_id == 0
 
@@ -253,6 +258,21 @@ def test_resource_rejections_come_from_the_compiled_kernels():
     # the method still accepts both: the oracle knows nothing of LDS
     orec = S.record(wide.cls, vec=8, stages=4, **rec)
     assert S.apply(orec, wide.cls, oshape(wide))["status"] == S.OK
+
+
+def test_depthwise_workgroup_size_is_limited_by_the_window_a_lane_holds():
+    """A workgroup of more than 512 threads leaves a lane 128 registers: the widest windows have no kernel there, the
+    method accepts the record all the same, and at 256 threads every window has one."""
+    dw = wl.Kernel(wl.CLS_DWCONV_BIAS_RELU6, wl.ConvShape(1, 128, 56, 56, 128, 3, 3, 2, 2, 1, 1))
+    for tile_k, tile_m, expect in ((8, 28, -1), (8, 8, 0)):
+        rec = dict(sketch=api.TT_SK_DWCONV, tile_m=tile_m, tile_n=28, tile_k=tile_k, wave_m=1, wave_n=7, mfma=0,
+                   vec=4, stages=1)
+        p = api.tt_schedule_apply(api.make_schedule(dw.cls, **rec), dw.cls, dw.shape)
+        assert p.status == api.TT_OK and p.block == tile_k * tile_m * 4 and p.variant_id == expect, (p.block, p.variant_id)
+        assert S.apply(S.record(dw.cls, S.SK_DWCONV, tile_m, 28, tile_k, 1, 7, 0, 1, 0, 4, 1, 1), dw.cls, oshape(dw))["status"] == S.OK
+    narrow = dict(sketch=api.TT_SK_DWCONV, tile_m=28, tile_n=4, tile_k=8, wave_m=1, wave_n=1, mfma=0, vec=1, stages=1)
+    p = api.tt_schedule_apply(api.make_schedule(dw.cls, **narrow), dw.cls, dw.shape)
+    assert p.status == api.TT_OK and p.block == 896 and p.variant_id == 0
 
 
 def test_ring_stages_are_reformulated_where_no_ring_kernel_applies():
