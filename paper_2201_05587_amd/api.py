@@ -525,8 +525,10 @@ def variant_name(plan: tt_plan, shape=None) -> str:
         return "tt::contract_kernel<" + ", ".join(str(v) for v in info[:9]) + ">"
     if plan.sketch == TT_SK_DWCONV:
         s = shape
+        bound = 256 if plan.block <= 256 else 512 if plan.block <= 512 else 1024   # the instance's thread bound
         if (s is not None and plan.stages == 1 and s.stride_h == s.stride_w and s.stride_h in (1, 2)
                 and s.n * s.h * s.w * s.c * 4 < 2 ** 31):
-            return f"tt::dwconv3x3_rows_kernel<{plan.wave_m}, {plan.wave_n}, {plan.eff_vec_a}, {s.stride_h}>"
-        return f"tt::dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}>"
+            return (f"tt::dwconv3x3_rows_kernel<{plan.wave_m}, {plan.wave_n}, {plan.eff_vec_a}, {s.stride_h}, "
+                    f"{bound}>")
+        return f"tt::dwconv3x3_kernel<{plan.wave_m}, {plan.wave_n}, {bound}>"
     return {TT_SK_GEMV: "tt::gemv_kernel", TT_SK_DIRECT: "tt::direct_kernel"}[plan.sketch]

@@ -69,8 +69,12 @@ def _symbol(name: str) -> str:
     name = name.strip()
     if name.startswith("void "):
         name = name[5:]
-    cut = name.find("(tt::ContractArgs")
-    return name[:cut] if cut >= 0 else name
+    name = name.replace("(anonymous namespace)::", "")
+    for args in ("(tt::ContractArgs", "(tt::DwArgs"):
+        cut = name.find(args)
+        if cut >= 0:
+            return name[:cut]
+    return name
 
 
 def per_symbol_kib(directory: str, counter: str) -> dict:
