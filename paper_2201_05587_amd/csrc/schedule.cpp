@@ -710,13 +710,31 @@ extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out
             if (!fam_ok) continue;
             // batch matmul records do not carry the layout: list each tile once (TN and NN tables are the same)
             if (cls == TT_BATCH_MATMUL && v.family == FAM_GEMM_NN) continue;
-            if (v.pipe != 0 || (v.family == FAM_CONV && v.amode != 16)) continue; // one pass per tile
+            // One pass per tile: the register-pipeline instance stands for the tile.  A tile that only the patch
+            // kernel is compiled for (its first instance stands for it) contributes its stages 5 and 6 alone.
+            bool patch_only = false;
+            if (v.pipe == 2) {
+                if (find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, 16, 0) >= 0)
+                    continue;
+                bool first = true;
+                for (int j = 0; j < i; ++j) {
+                    const Variant &u = kVariants[j];
+                    if (u.pipe == 2 && u.dtype == v.dtype && u.tile_m == v.tile_m && u.tile_n == v.tile_n &&
+                        u.tile_k == v.tile_k && u.wave_m == v.wave_m && u.wave_n == v.wave_n && u.mfma == v.mfma)
+                        first = false;
+                }
+                if (!first) continue;
+                patch_only = true;
+            } else if (v.pipe != 0 || (v.family == FAM_CONV && v.amode != 16)) {
+                continue;
+            }
             static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 32};
             const int n_split = level >= 1 ? 9 : 1;
             const int n_order = level >= 2 ? 6 : (level >= 1 ? 2 : 1);
             for (int si = 0; si < n_split; ++si)
                 for (int order = 0; order < n_order; ++order)
                     for (int stages = (level >= 1 ? 1 : 2); stages <= (level >= 1 ? 6 : 2); ++stages) {
+                        if (patch_only && stages < 5) continue;
                         // three and four stages only for tiles the asynchronous pipeline can load, five and six
                         // only for tiles the patch kernel is compiled for
                         if ((stages == 3 || stages == 4) &&

@@ -224,6 +224,22 @@ def test_schedule_space_is_well_formed_and_contains_the_default_tiles():
         for r in space:
             assert S.record_is_well_formed(r.knobs()), r
             assert r.cls == cls
+    # every tile the patch kernel is compiled for is in the space with stages 5 and 6, also where no other
+    # kernel implements the tile (then with those stages only), and no record is listed twice
+    space = api.tt_schedule_space(wl.CLS_CONV2D_BIAS_RELU, wl.BF16, 2)
+    keys = [tuple(r.knobs().values()) for r in space]
+    assert len(set(keys)) == len(keys)
+    tile = lambda r: (r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma)
+    stages_of = {}
+    for r in space:
+        stages_of.setdefault(tile(r), set()).add(r.stages)
+    patch_tiles = {tuple(v[f] for f in ("tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfma"))
+                   for v in all_variants() if v["pipe"] == 2}
+    assert len(patch_tiles) >= 8
+    for t in patch_tiles:
+        assert {5, 6} <= stages_of[t], t
+    assert any(stages_of[t] == {5, 6} for t in patch_tiles)
+    assert all(({5, 6} & st) == set() or t in patch_tiles for t, st in stages_of.items())
     # every default matrix-core record of the configured shapes has a compiled variant
     for k in all_cfg_kernels():
         rec = api.tt_schedule_default(k.cls, k.shape)
