@@ -171,6 +171,27 @@ def chain_leg(args, api, harness, tune, wl, targets, dks, transfer):
                                 "chained_over_standalone": chain_us / standalone_us}}))
 
 
+def machine_rates(api):
+    """What plain kernels reach on this GPU (tt_debug_probe), to set beside the roofline fractions."""
+    import torch
+    n = 768 << 20                                    # per buffer: a copy streams 1.5 GB, six times the memory-side cache
+    src = torch.ones(n // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    small = torch.ones((2 << 20) // 4, dtype=torch.int32, device="cuda")
+    r = dict(
+        launch_gap_us=api.tt_debug_probe(api.TT_PROBE_LAUNCH_GAP_US, reps=200),
+        mfma_bf16_tflops=api.tt_debug_probe(api.TT_PROBE_MFMA_BF16_TFLOPS, dst=small, reps=5),
+        copy_linear_cold_gbps=api.tt_debug_probe(api.TT_PROBE_COPY_LINEAR_GBPS, src, dst, reps=4),
+        copy_tiled_cold_gbps=api.tt_debug_probe(api.TT_PROBE_COPY_TILED_GBPS, src, dst, reps=4),
+        l2_read_gbps=api.tt_debug_probe(api.TT_PROBE_L2_READ_GBPS, small, dst, reps=5),
+        what="plain kernels of the library timed like the operators: empty launches back to back; 32x32x16 bf16 MFMA "
+             "only; read+write rate of a 768 MiB copy, linear and in 64-row x 128-byte tiles of 512-byte rows; reads "
+             "of a 2 MiB source by all CUs")
+    del src, dst, small
+    torch.cuda.empty_cache()
+    return r
+
+
 def cpu_baseline_leg(wl, targets, budget_s=25.0):
     """The oracle, as it stands, on the host cores: each distinct kernel of the workload once, largest first,
     until the time budget is spent."""
@@ -436,6 +457,7 @@ def main():
         "sweep": sweep,
         "roofline": roof,
     }
+    out["machine_rates"] = machine_rates(api)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_leg(wl, targets)
     report = os.path.join(ROOT, "gpurun_out", f"bench_{args.workload}_kernels.json")

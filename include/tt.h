@@ -243,6 +243,32 @@ int tt_debug_tile_map(const tt_plan *plan, int32_t *out_dev, void *stream);
 int64_t tt_debug_fast_div(uint32_t n, uint32_t d);
 
 /*
+ * Debug: hardware-rate probes.  Each runs a plain hand-written kernel `reps` times back to back on
+ * `stream` (after one untimed run), times the run with events on that stream, synchronises, and writes one
+ * figure to *result.  They measure the machine, not the method: a kernel's roofline fraction can be put
+ * next to the rate the simplest kernel of its kind reaches on the same GPU.
+ *   TT_PROBE_LAUNCH_GAP_US     microseconds per launch of an empty kernel (src, dst, bytes unused)
+ *   TT_PROBE_MFMA_BF16_TFLOPS  32x32x16 bf16 matrix products issued back to back by four waves per SIMD;
+ *                              dst: at least 1 KB of device memory (never written), bytes its size
+ *   TT_PROBE_COPY_LINEAR_GBPS  copy of `bytes` (a multiple of 32 KiB) from src to dst, 16 bytes per lane,
+ *                              consecutive lanes on consecutive addresses; result = 2 * bytes / time
+ *   TT_PROBE_COPY_TILED_GBPS   the same bytes as a matrix of 512-byte rows copied in tiles of 64 rows x 128
+ *                              bytes per workgroup (the order in which a contraction's epilogue writes)
+ *   TT_PROBE_L2_READ_GBPS      1024 workgroups read 4 MiB each out of a source of 1..2 MiB (`bytes`) that
+ *                              stays in the L2; dst: at least 1 KB of device memory (never written)
+ * src and dst are device pointers, 16-byte aligned, owned by the caller; a cold copy figure needs buffers
+ * larger than the caches.  TT_ERR_BAD_ARG for sizes or pointers outside these rules.
+ */
+enum {
+    TT_PROBE_LAUNCH_GAP_US = 0,
+    TT_PROBE_MFMA_BF16_TFLOPS = 1,
+    TT_PROBE_COPY_LINEAR_GBPS = 2,
+    TT_PROBE_COPY_TILED_GBPS = 3,
+    TT_PROBE_L2_READ_GBPS = 4
+};
+int tt_debug_probe(int which, const void *src, void *dst, size_t bytes, int reps, void *stream, double *result);
+
+/*
  * conv2d (+bias) (+residual) (+activation) as an implicit GEMM (Algorithm 2; Table 1
  * classes A, E, F).  cls selects the epilogue: TT_CONV2D_ADD (bias, none),
  * TT_CONV2D_BIAS_RELU, TT_CONV2D_BIAS_ADD_RELU (residual required, same layout

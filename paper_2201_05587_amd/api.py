@@ -94,7 +94,7 @@ class tt_sweep_row(Structure):
 
 
 EXPORTS = ("tt_version", "tt_status_name", "tt_last_error", "tt_schedule_default", "tt_schedule_apply", "tt_plan_tile",
-           "tt_debug_tile_map", "tt_debug_fast_div", "tt_conv2d_bias_relu", "tt_conv2d_bias_relu_noalloc", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
+           "tt_debug_tile_map", "tt_debug_fast_div", "tt_debug_probe", "tt_conv2d_bias_relu", "tt_conv2d_bias_relu_noalloc", "tt_dense_bias_relu", "tt_batch_matmul", "tt_dwconv",
            "tt_transfer_sweep", "tt_sweep_plan", "tt_refine_space", "tt_refine", "tt_native_sweep", "tt_time_pair", "tt_run_kernels", "tt_schedule_space", "tt_sweep_select", "tt_variant_info", "tt_num_variants", "tt_select_donor")
 
 
@@ -147,6 +147,7 @@ def _load():
     for name in EXPORTS:
         if name not in ("tt_status_name", "tt_last_error", "tt_debug_fast_div"):
             getattr(lib, name).restype = ctypes.c_int
+    lib.tt_debug_probe.argtypes = [ctypes.c_int, c_void_p, c_void_p, c_size_t, ctypes.c_int, c_void_p, POINTER(c_double)]
     lib.tt_debug_fast_div.restype = c_int64
     lib.tt_debug_fast_div.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
     return lib
@@ -354,6 +355,20 @@ def tt_debug_tile_map(plan):
     _check(lib.tt_debug_tile_map(byref(plan), _ptr(out), _stream()), "tt_debug_tile_map")
     torch.cuda.synchronize()
     return out.cpu().numpy()
+
+
+TT_PROBE_LAUNCH_GAP_US, TT_PROBE_MFMA_BF16_TFLOPS, TT_PROBE_COPY_LINEAR_GBPS, TT_PROBE_COPY_TILED_GBPS, \
+    TT_PROBE_L2_READ_GBPS = range(5)
+
+
+def tt_debug_probe(which, src=None, dst=None, reps=10):
+    """One hardware-rate figure (see tt.h); src and dst are device tensors where the probe needs them."""
+    out = c_double(0.0)
+    nbytes = (src if src is not None else dst)
+    nbytes = nbytes.numel() * nbytes.element_size() if nbytes is not None else 0
+    _check(lib.tt_debug_probe(which, _ptr(src) if src is not None else None, _ptr(dst) if dst is not None else None,
+                              nbytes, reps, _stream(), byref(out)), "tt_debug_probe")
+    return out.value
 
 
 class DeviceKernel:

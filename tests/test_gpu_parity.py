@@ -507,3 +507,26 @@ def test_patch_kernel_is_the_one_that_runs_where_it_applies(api):
         plan = api.tt_schedule_apply(rec, k.cls, k.shape)
         ran.append(api.tt_variant_info(plan.variant_id)[9])
     assert ran.count(2) == len(PATCH_CASES) - 1 and ran[5] == 1
+
+
+def test_machine_rate_probes_copy_exactly_and_report_plausible_rates(api):
+    """The probes are plain kernels: the copies must reproduce their source, every rate must be positive and below
+    what the hardware can do, and bad arguments are refused before anything is launched."""
+    import torch
+    n = 64 << 20
+    src = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+    for which in (api.TT_PROBE_COPY_LINEAR_GBPS, api.TT_PROBE_COPY_TILED_GBPS):
+        dst = torch.zeros_like(src)
+        gbps = api.tt_debug_probe(which, src, dst, reps=3)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+        assert 100.0 < gbps < 2.0e4, gbps
+    small = torch.ones((1 << 20) // 4, dtype=torch.int32, device="cuda")
+    assert 0.5 < api.tt_debug_probe(api.TT_PROBE_LAUNCH_GAP_US, reps=50) < 100.0
+    assert 100.0 < api.tt_debug_probe(api.TT_PROBE_MFMA_BF16_TFLOPS, dst=small, reps=2) < 3000.0
+    assert 1.0e3 < api.tt_debug_probe(api.TT_PROBE_L2_READ_GBPS, small, dst, reps=2) < 2.0e5
+    odd = torch.ones(1000, dtype=torch.int32, device="cuda")
+    with pytest.raises(api.TTError):
+        api.tt_debug_probe(api.TT_PROBE_COPY_LINEAR_GBPS, odd, odd, reps=1)
+    with pytest.raises(api.TTError):
+        api.tt_debug_probe(99, src, dst, reps=1)
