@@ -136,7 +136,13 @@ typedef struct tt_gemm_shape {
  *                workgroup tile, i.e. the tile's padded input patch cached in LDS for tile_k channels at
  *                a time, plus a ring of 3 or 4 filter buffers (reformulated to 3 or 4 where it does
  *                not apply: other filters or data types, a patch larger than the kernel's buffer, a
- *                channel count tile_k does not divide, a split off the channel-slice boundaries).
+ *                channel count tile_k does not divide, a split off the channel-slice boundaries);
+ *                7 = dense family with a short reduction (dense layers, unit-stride 1x1 convolutions,
+ *                A.B^T products of one batch): cache buffer + ComputeAt one level further out, the whole
+ *                [tile_n][K] panel of the second operand cached in LDS once per workgroup, which then
+ *                walks down M with the first operand's rows double-buffered a tile ahead
+ *                (reformulated to 4 where it does not apply: K not a whole number of tile_k slices or
+ *                too long for the LDS, a split reduction, several batches, partial 16-byte items).
  *   TT_SK_GEMV   tile_m (= wave_m) rows and tile_n outputs per workgroup, wave_n outputs per wave,
  *                tile_k = K elements a wave consumes per step (64 lanes x 1/2/4/8), mfma = 0.
  *   TT_SK_DWCONV tile_m x tile_n output rows x cols and tile_k lanes along the plane axis per workgroup,
@@ -156,7 +162,7 @@ typedef struct tt_schedule {
     int32_t order;  /* 0 M-tiles fastest, 1 N-tiles fastest, 2 bands of 8 M-tiles; +3 = XCD-contiguous */
     int32_t vec;    /* 1, 2, 4 or 8 */
     int32_t unroll; /* >= 1 */
-    int32_t stages; /* 1..6 (matrix-core sketch), 1 or 2 (others) */
+    int32_t stages; /* 1..7 (matrix-core sketch), 1 or 2 (others) */
     /* provenance (ignored by tt_schedule_apply): */
     int32_t id;              /* caller's identifier of the record                     */
     int32_t donor_shape[12]; /* the shape the record was tuned on (struct as int32[]) */
@@ -173,7 +179,8 @@ typedef struct tt_schedule {
  *   library  how this library's kernels fetch and stage the tiles: eff_vec_*, eff_unroll, stages
  *            (after reformulation), lds_bytes, variant_id, and the reasons TT_R_LDS and
  *            TT_R_K_GRANULE, which are checked after every method rule.  lds_bytes is stages times
- *            the per-stage size the compiled kernel variant reports (tt_variant_info); it is 0 when
+ *            the per-stage size the compiled kernel variant reports (tt_variant_info; the kernels of
+ *            stages 5..7 report their own layouts); it is 0 when
  *            no variant implements the plan (variant_id = -1: the operator entry points then return
  *            TT_ERR_UNSUPPORTED).
  */

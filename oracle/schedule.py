@@ -232,7 +232,7 @@ def record_is_well_formed(rec: dict) -> bool:
         return False
     if rec["split_k"] < 1 or rec["order"] < 0 or rec["order"] >= 6 or rec["vec"] not in (1, 2, 4, 8):
         return False
-    if rec["unroll"] < 1 or rec["stages"] < 1 or rec["stages"] > (6 if sk == SK_MFMA else 2):
+    if rec["unroll"] < 1 or rec["stages"] < 1 or rec["stages"] > (7 if sk == SK_MFMA else 2):
         return False
     tm, tn, tk, wm, wn, mf = (rec[f] for f in ("tile_m", "tile_n", "tile_k", "wave_m", "wave_n", "mfma"))
     if sk == SK_MFMA:

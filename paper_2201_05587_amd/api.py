@@ -535,6 +535,8 @@ def variant_name(plan: tt_plan, shape=None) -> str:
             stride = shape.stride_h if shape is not None else 0
             return (f"tt::conv3x3_patch_kernel<{info[2]}, {info[3]}, {info[4]}, {info[5]}, {info[6]}, {stride}, "
                     f"{per_thread}>")
+        if info[9] == 3:
+            return "tt::gemm_stream_kernel<" + ", ".join(str(info[i]) for i in (0, 2, 3, 4, 5, 6, 7)) + ">"
         if info[9]:
             return "tt::contract_async_kernel<" + ", ".join(str(v) for v in info[:8]) + ">"
         return "tt::contract_kernel<" + ", ".join(str(v) for v in info[:9]) + ">"

@@ -616,7 +616,11 @@ __device__ __forceinline__ void load_res_early(ResRegs<DT, TM, WM, WN, MF, ALLOW
     }
 }
 
-template <int DT, int TM, int WM, int WN, int MF, typename Acc, bool ALLOW>
+template <int N> __device__ __forceinline__ void wait_loads_outstanding(); // (defined with the asynchronous loaders)
+
+// WAIT_LOADS: the caller has asynchronous requests in flight that must have landed before the first store
+// is issued (a persistent kernel's next tile); the wait sits behind the staging of the first band.
+template <int DT, int TM, int WM, int WN, int MF, typename Acc, bool ALLOW, bool WAIT_LOADS = false>
 __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const ContractArgs &g, const TileCoord &tc,
                                            unsigned char *smem, int wave, int lane, const BiasRegs<DT> &bias,
                                            const ResRegs<DT, TM, WM, WN, MF, ALLOW> &early)
@@ -677,6 +681,8 @@ __device__ __forceinline__ void write_tile(Acc (&acc)[WM / MF][WN / MF], const C
                 stage[row_l * ESTRIDE + j * MF + lane_r] = acc[i][j][v];
             }
         asm volatile("" ::: "memory"); // and the reads below stay behind them
+        if constexpr (WAIT_LOADS)
+            if (i == 0) wait_loads_outstanding<0>();
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
             if (!T::pass_live(lane, ps)) continue;

@@ -49,6 +49,23 @@ PATCH_TILES = [
 ]
 
 
+# persistent contraction for short reductions (dense family; record knob stages = 7):
+# (tile_m, tile_n, wave_m, wave_n), each with both matrix-core blocks and the tile_k list of its data type
+STREAM_TILES = [(64, 128, 32, 64), (32, 128, 32, 32), (64, 64, 32, 32), (128, 64, 32, 32), (128, 128, 32, 64)]
+
+
+def stream_variants():
+    out = []
+    for dt in (F32, BF16):
+        for tm, tn, wm, wn in STREAM_TILES:
+            assert (tm, tn, wm, wn) in TILES_FULL  # the record space lists a tile through its register-pipeline instance
+            for mf in (16, 32):
+                for tk in ((16, 32) if dt == F32 else (32, 64)):
+                    if async_ok(dt, 1, tm, tn, tk, wm, wn, 0):
+                        out.append((dt, 1, tm, tn, tk, wm, wn, mf, 0, 3, 0))
+    return out
+
+
 def patch_variants():
     seen, out = set(), []
     for tm, tn, ck, wm, wn, stride, pl in PATCH_TILES:
@@ -101,7 +118,7 @@ def variants(which):
     skip = spilling()
     out = [v for v in out if not (v[9] == 0 and ("contract_kernel", v[:9]) in skip)]
     patch = [v for v in patch_variants() if ("conv3x3_patch_kernel", (v[2], v[3], v[4], v[5], v[6], v[10], v[11])) not in skip]
-    return out + patch
+    return out + patch + stream_variants()
 
 
 def async_ok(dt, fam, tm, tn, tk, wm, wn, am):
@@ -125,12 +142,16 @@ def main():
         slices[i % n_slices].append((i, v))
     for s, items in enumerate(slices):
         lines = ['// generated by gen_variants.py - do not edit', '#include "../contract.hip.h"',
-                 '#include "../conv_patch.hip.h"', "namespace tt {"]
+                 '#include "../conv_patch.hip.h"', '#include "../stream_gemm.hip.h"', "namespace tt {"]
         for i, v in items:
             if v[9] == 2:
                 args = ", ".join(str(x) for x in (v[2], v[3], v[4], v[5], v[6], v[10], v[11]))
                 call, size, lds = (f"launch_conv_patch<{args}>", f"capacity_conv_patch<{args}>",
                                    f"lds_bytes_conv_patch<{args}>")
+            elif v[9] == 3:
+                args = ", ".join(str(x) for x in (v[0], v[2], v[3], v[4], v[5], v[6], v[7]))
+                call, size, lds = (f"launch_gemm_stream<{args}>", f"requests_gemm_stream<{args}>",
+                                   f"lds_bytes_gemm_stream<{args}>")
             elif v[9] == 1:
                 args = ", ".join(str(x) for x in v[:8])
                 call, size, lds = (f"launch_contract_async<{args}>", f"stage_bytes_contract_async<{args}>",

@@ -73,7 +73,7 @@ bool record_well_formed(const tt_schedule &r)
     if (r.sketch < TT_SK_MFMA || r.sketch > TT_SK_DIRECT) return false;
     if (r.split_k < 1 || r.order < 0 || r.order >= 6) return false;
     if (r.vec != 1 && r.vec != 2 && r.vec != 4 && r.vec != 8) return false;
-    if (r.unroll < 1 || r.stages < 1 || r.stages > (r.sketch == TT_SK_MFMA ? 6 : 2)) return false;
+    if (r.unroll < 1 || r.stages < 1 || r.stages > (r.sketch == TT_SK_MFMA ? 7 : 2)) return false;
     switch (r.sketch) {
     case TT_SK_MFMA: {
         if (r.mfma != 16 && r.mfma != 32) return false;
@@ -417,6 +417,29 @@ extern "C" int tt_schedule_apply(const tt_schedule *sched, int cls, const void *
     // reduction that fall on channel-slice boundaries, and tiles whose patch fits the compiled buffer;
     // elsewhere the record is reformulated to the plain ring of stages - 2 buffers.
     int want = r.stages;
+    // Seven stages ask for the persistent kernel of the dense family: the whole [tile_n][K] panel of B stays
+    // in LDS, a workgroup walks down M with the next tile's A rows requested a tile ahead.  It exists for
+    // reductions of a few whole slices (the panel, two A buffers and the epilogue's staging must fit the LDS,
+    // the requests the vector-memory counter), one batch, no split of the reduction, whole 16-byte items;
+    // elsewhere the record is reformulated to the ring of four buffers.
+    if (want == 7) {
+        int stream_id = -1;
+        if (family == FAM_GEMM_TN && whole_items && in_range && e.batch == 1 && p.eff_split_k == 1 && e.K % r.tile_k == 0)
+            stream_id = find_variant(dt, FAM_GEMM_TN, r.tile_m, r.tile_n, r.tile_k, r.wave_m, r.wave_n, r.mfma, 0, 3);
+        if (stream_id >= 0) {
+            const Variant &v = kVariants[stream_id];
+            if (v.lds_bytes(p.k_tiles) > kLdsBudget || (int64_t)p.k_tiles * v.stage_bytes() + 8 > 63) stream_id = -1;
+        }
+        if (stream_id >= 0) {
+            p.stages = 7;
+            p.eff_unroll = std::min(r.unroll, r.tile_k / granule);
+            p.variant_id = stream_id;
+            p.lds_bytes = kVariants[stream_id].lds_bytes(p.k_tiles);
+            *plan = p;
+            return TT_OK;
+        }
+        want = 4;
+    }
     if (want >= 5) {
         int patch_id = -1;
         if (is_conv_class(cls) && dt == TT_BF16 && r.mfma == 32 && whole_items && amode == 16) {
@@ -733,14 +756,19 @@ extern "C" int tt_schedule_space(int cls, int dtype, int level, tt_schedule *out
             const int n_order = level >= 2 ? 6 : (level >= 1 ? 2 : 1);
             for (int si = 0; si < n_split; ++si)
                 for (int order = 0; order < n_order; ++order)
-                    for (int stages = (level >= 1 ? 1 : 2); stages <= (level >= 1 ? 6 : 2); ++stages) {
-                        if (patch_only && stages < 5) continue;
+                    for (int stages = (level >= 1 ? 1 : 2); stages <= (level >= 1 ? 7 : 2); ++stages) {
+                        if (patch_only && (stages < 5 || stages > 6)) continue;
+                        // seven stages only for tiles the persistent kernel is compiled for, unsplit
+                        if (stages == 7 &&
+                            (splits[si] != 1 ||
+                             find_variant(v.dtype, FAM_GEMM_TN, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, 0, 3) < 0))
+                            continue;
                         // three and four stages only for tiles the asynchronous pipeline can load, five and six
                         // only for tiles the patch kernel is compiled for
                         if ((stages == 3 || stages == 4) &&
                             find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, v.amode, 1) < 0)
                             continue;
-                        if (stages >= 5 &&
+                        if ((stages == 5 || stages == 6) &&
                             find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, 16, 2, 1) < 0 &&
                             find_variant(v.dtype, v.family, v.tile_m, v.tile_n, v.tile_k, v.wave_m, v.wave_n, v.mfma, 16, 2, 2) < 0)
                             continue;

@@ -185,10 +185,13 @@ struct Variant {
     int32_t amode; // conv family: bytes per gathered load (16 or the element size); 0 otherwise
     int32_t pipe;  // 0: register-staged loads, 1 or 2 LDS stages; 1: asynchronous loads into a ring of 3 or 4;
                    // 2: 3x3 conv with the padded input patch in LDS and a filter ring of 3 or 4 (stages 5 or 6)
+                   // 3: persistent dense kernel, the B panel resident in LDS and two A buffers (stages 7)
     int32_t stride; // pipe 2: the convolution stride the kernel is compiled for; 0 otherwise
     int (*launch)(const ContractArgs &args, int grid, int lds_bytes, void *stream);
-    int (*stage_bytes)();        // pipes 0, 1: LDS bytes of one pipeline stage; pipe 2: pixels a patch buffer holds
-    int (*lds_bytes)(int stages); // LDS bytes for a plan's number of stages, as the compiled kernel lays LDS out
+    int (*stage_bytes)();        // pipes 0, 1: LDS bytes of one pipeline stage; pipe 2: pixels a patch buffer holds;
+                                 // pipe 3: request instructions per lane and K slice
+    int (*lds_bytes)(int stages); // LDS bytes for a plan's number of stages (pipe 3: for its number of K slices), as
+                                  // the compiled kernel lays LDS out
 };
 
 // Reduction elements one 16-byte operand fragment per lane feeds to the matrix cores: a block of MF rows

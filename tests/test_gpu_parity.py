@@ -509,6 +509,46 @@ def test_patch_kernel_is_the_one_that_runs_where_it_applies(api):
     assert ran.count(2) == len(PATCH_CASES) - 1 and ran[5] == 1
 
 
+# ---- persistent kernel of the dense family: B panel resident in LDS (stages 7) ------------------------
+STREAM_CASES = [
+    # kernel, (tile_m, tile_n, tile_k, wave_m, wave_n, mfma)
+    # 1x1 convolution with residual, one slice; 1568 tiles for 512 resident workgroups: three tiles each
+    (wl.Kernel(wl.CLS_CONV2D_BIAS_ADD_RELU, wl.ConvShape(16, 64, 56, 56, 256, 1, 1, 1, 1, 0, 0, wl.BF16), 1, "pw_res"),
+     (64, 128, 64, 32, 64, 32)),
+    # ragged M (1 x 37 x 37 = 1369 rows) and a ragged last panel (N = 200), two slices, 16-blocks
+    (wl.Kernel(wl.CLS_CONV2D_BIAS_RELU, wl.ConvShape(1, 128, 37, 37, 200, 1, 1, 1, 1, 0, 0, wl.BF16), 1, "pw_ragged"),
+     (64, 128, 64, 32, 64, 16)),
+    # fewer tiles than resident workgroups: some workgroups get one tile, the loop of none runs twice
+    (wl.Kernel(wl.CLS_DENSE_BIAS_GELU, wl.GemmShape(1, 300, 256, 256, 1, wl.BF16), 1, "dense_few_tiles"),
+     (32, 128, 64, 32, 32, 16)),
+    # four slices of 64, linear epilogue, rows that are not whole vectors long (N = 70: element path)
+    (wl.Kernel(wl.CLS_DENSE_ADD, wl.GemmShape(1, 5000, 70, 256, 1, wl.BF16), 1, "dense_narrow"),
+     (64, 64, 64, 32, 32, 32)),
+    # one-batch A.B^T product, no bias at all
+    (wl.Kernel(wl.CLS_BATCH_MATMUL, wl.GemmShape(1, 2048, 384, 128, 1, wl.BF16), 1, "bmm_one_batch"),
+     (128, 64, 64, 32, 32, 16)),
+    # fp32: pointwise ReLU6 with ragged everything, a dense layer on eight waves, and one on 32-blocks
+    (wl.Kernel(wl.CLS_CONV2D_BIAS_RELU6, wl.ConvShape(3, 96, 29, 29, 144, 1, 1, 1, 1, 0, 0, wl.F32), 1, "pw_f32"),
+     (64, 128, 32, 32, 64, 16)),
+    (wl.Kernel(wl.CLS_DENSE_BIAS_RELU, wl.GemmShape(1, 4100, 128, 64, 1, wl.F32), 1, "dense_f32"),
+     (128, 128, 16, 32, 64, 16)),
+    (wl.Kernel(wl.CLS_DENSE_BIAS_RELU, wl.GemmShape(1, 9000, 192, 64, 1, wl.F32), 1, "dense_f32_blocks32"),
+     (64, 64, 32, 32, 32, 32)),
+]
+
+
+@pytest.mark.parametrize("case", STREAM_CASES, ids=[c[0].name for c in STREAM_CASES])
+def test_persistent_dense_kernel_with_the_panel_in_lds(api, P, case):
+    k, (tm, tn, tk, wm, wn, mf) = case
+    vec = 8 if k.shape.dtype == wl.BF16 else 4
+    recs = [mfma(api, k.cls, tm, tn, tk, wm, wn, mf, order=o, vec=vec, stages=7) for o in (0, 4)]
+    for rec in recs:
+        plan = api.tt_schedule_apply(rec, k.cls, k.shape)
+        assert plan.status == api.TT_OK and plan.stages == 7 and api.tt_variant_info(plan.variant_id)[9] == 3, \
+            (plan.status, plan.reason, plan.stages, plan.variant_id)
+    P.check_kernel(k, recs, seed=707)
+
+
 def test_machine_rate_probes_copy_exactly_and_report_plausible_rates(api):
     """The probes are plain kernels: the copies must reproduce their source, every rate must be positive and below
     what the hardware can do, and bad arguments are refused before anything is launched."""

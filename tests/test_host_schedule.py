@@ -92,7 +92,7 @@ def random_record(rng, cls):
     mf = rng.choice([16, 32])
     return S.record(cls, S.SK_MFMA, tm, tn, rng.choice([16, 32, 64, 128]), rng.choice([16, 32, 64, 128]),
                     rng.choice([16, 32, 64, 128]), mf, rng.choice([1, 1, 2, 3, 4, 8, 16, 64]), rng.randrange(6),
-                    rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 512]), rng.choice([1, 2, 3, 4, 5, 6]))
+                    rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 512]), rng.choice([1, 2, 3, 4, 5, 6, 7]))
 
 
 def test_apply_matches_oracle_bit_for_bit_on_random_records():
@@ -135,15 +135,22 @@ def check_library_fields(cplan, rec, k):
             v = getattr(cplan, f)
             assert v == S.pow2_dividing(min(rec["vec"], widest), extent), (f, v, rec["vec"], extent)
         assert 1 <= cplan.eff_unroll <= rec["unroll"]
-        # reformulation chain of the cache-buffer knob: patch + ring (5, 6) -> ring (3, 4) -> two register stages
-        assert cplan.stages in {rec["stages"]} | ({rec["stages"] - 2, 2} if rec["stages"] >= 5 else set()) | \
-            ({2} if rec["stages"] >= 3 else set())
+        # reformulation chain of the cache-buffer knob: resident panel (7) -> ring of four; patch + ring (5, 6) ->
+        # ring (3, 4) -> two register stages
+        assert cplan.stages in {rec["stages"]} | ({4, 2} if rec["stages"] == 7 else set()) | \
+            ({rec["stages"] - 2, 2} if rec["stages"] in (5, 6) else set()) | ({2} if rec["stages"] >= 3 else set())
         if cplan.variant_id >= 0:
             v = dict(zip(api.VARIANT_INFO, api.tt_variant_info(cplan.variant_id)))
             assert (v["dtype"], v["tile_m"], v["tile_n"], v["tile_k"], v["wave_m"], v["wave_n"], v["mfma"]) == \
                 (s.dtype, rec["tile_m"], rec["tile_n"], rec["tile_k"], rec["wave_m"], rec["wave_n"], rec["mfma"])
-            assert v["pipe"] == (2 if cplan.stages >= 5 else 1 if cplan.stages >= 3 else 0)
-            if v["pipe"] < 2:
+            assert v["pipe"] == (3 if cplan.stages == 7 else 2 if cplan.stages >= 5 else 1 if cplan.stages >= 3 else 0)
+            if v["pipe"] == 3:
+                # the whole panel of B, two A buffers and the epilogue's staging; requests within the counter
+                es = 4 if s.dtype == wl.F32 else 2
+                assert 160 * 1024 >= cplan.lds_bytes > cplan.k_tiles * (rec["tile_n"] + 2 * rec["tile_m"]) * rec["tile_k"] * es
+                assert cplan.K % rec["tile_k"] == 0 and cplan.batch == 1 and cplan.eff_split_k == 1
+                assert cplan.k_tiles * v["stage_bytes"] + 8 <= 63
+            elif v["pipe"] < 2:
                 assert cplan.lds_bytes == cplan.stages * v["stage_bytes"] <= 160 * 1024
             else:
                 # two patch buffers of the exported pixel capacity and a ring of stages - 2 filter tiles
@@ -153,7 +160,8 @@ def check_library_fields(cplan, rec, k):
             assert rec["tile_k"] % v["k_granule"] == 0
             assert cplan.eff_unroll == min(rec["unroll"], rec["tile_k"] // v["k_granule"])
             # a stage holds at least the two operand tiles
-            assert v["stage_bytes"] >= (rec["tile_m"] + rec["tile_n"]) * rec["tile_k"] * (4 if s.dtype == wl.F32 else 2)
+            assert v["pipe"] == 3 or \
+                v["stage_bytes"] >= (rec["tile_m"] + rec["tile_n"]) * rec["tile_k"] * (4 if s.dtype == wl.F32 else 2)
         else:
             assert cplan.lds_bytes == 0
     elif cplan.sketch == api.TT_SK_DWCONV:
@@ -309,8 +317,38 @@ def test_ring_stages_are_reformulated_where_no_ring_kernel_applies():
     bm = wl.CLS_BATCH_MATMUL
     assert api.tt_schedule_apply(api.make_schedule(bm, stages=3, **rec), bm, wl.GemmShape(4, 128, 128, 64, 0, bf)).stages == 2
     assert api.tt_schedule_apply(api.make_schedule(bm, stages=3, **rec), bm, wl.GemmShape(4, 128, 128, 64, 1, bf)).stages == 3
-    # seven stages is not a record
-    assert api.tt_schedule_apply(api.make_schedule(E, stages=7, **rec), E, conv).status == api.TT_ERR_BAD_ARG
+    # eight stages is not a record
+    assert api.tt_schedule_apply(api.make_schedule(E, stages=8, **rec), E, conv).status == api.TT_ERR_BAD_ARG
+
+
+def test_resident_panel_stage_applies_to_short_dense_reductions_and_is_reformulated_elsewhere():
+    bf = wl.BF16
+    E, D = wl.CLS_CONV2D_BIAS_RELU, wl.CLS_DENSE_ADD
+    rec = dict(tile_m=64, tile_n=128, tile_k=64, wave_m=32, wave_n=64, mfma=32, vec=8, unroll=8)
+    pipe = lambda p: api.tt_variant_info(p.variant_id)[9]
+    # a unit-stride 1x1 convolution is a dense product: K = 64 is one slice
+    pw = wl.ConvShape(32, 64, 56, 56, 256, 1, 1, 1, 1, 0, 0, bf)
+    p = api.tt_schedule_apply(api.make_schedule(E, stages=7, **rec), E, pw)
+    assert (p.status, p.stages, pipe(p), p.k_tiles) == (api.TT_OK, 7, 3, 1) and 0 < p.lds_bytes <= 160 * 1024
+    # the method part of the plan does not depend on the stage knob
+    q = api.tt_schedule_apply(api.make_schedule(E, stages=4, **rec), E, pw)
+    assert p.method() == q.method() and (q.stages, pipe(q)) == (4, 1)
+    # a 3x3 filter, a stride, a split reduction, several batches, a K that is not whole slices, a K too long for
+    # the LDS: the ring of four (or what the ring falls back to)
+    for cls, shape, extra in ((E, wl.ConvShape(32, 64, 56, 56, 256, 3, 3, 1, 1, 1, 1, bf), {}),
+                              (E, wl.ConvShape(32, 64, 56, 56, 256, 1, 1, 2, 2, 0, 0, bf), {}),
+                              (D, wl.GemmShape(1, 4096, 256, 128, 1, bf), dict(split_k=2)),
+                              (wl.CLS_BATCH_MATMUL, wl.GemmShape(4, 4096, 256, 64, 1, bf), {}),
+                              (D, wl.GemmShape(1, 4096, 256, 96, 1, bf), {}),
+                              (D, wl.GemmShape(1, 4096, 256, 1024, 1, bf), {})):
+        p = api.tt_schedule_apply(api.make_schedule(cls, stages=7, **dict(rec, **extra)), cls, shape)
+        assert p.status == api.TT_OK and p.stages in (4, 2) and pipe(p) in (0, 1), (shape, p.stages)
+    # dense and one-batch A.B^T products qualify
+    for cls, shape in ((D, wl.GemmShape(1, 4096, 256, 128, 1, bf)), (wl.CLS_BATCH_MATMUL, wl.GemmShape(1, 4096, 256, 64, 1, bf))):
+        p = api.tt_schedule_apply(api.make_schedule(cls, stages=7, **rec), cls, shape)
+        assert (p.status, p.stages, pipe(p)) == (api.TT_OK, 7, 3)
+    # the oracle accepts the record like any other stage count
+    assert S.apply(S.record(D, S.SK_MFMA, 64, 128, 64, 32, 64, 32, 1, 0, 8, 8, 7), D, oshape(wl.Kernel(D, wl.GemmShape(1, 4096, 256, 128, 1, bf))))["status"] == S.OK
 
 
 def test_patch_stages_apply_to_3x3_bf16_convolutions_and_are_reformulated_elsewhere():
