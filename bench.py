@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--level", type=int, default=1, help="size of the enumerated native space (0, 1, 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-live-sweep", action="store_true", help="do not repeat the sweeps after the timed region")
+    ap.add_argument("--sweep-cold-mb", type=int, default=600,
+                    help="megabytes of tensor sets the sweeps' launches rotate through (0: one set, cache-warm timing)")
     ap.add_argument("--kernels", default="", help="comma-separated kernel names: restrict the workload to them")
     ap.add_argument("--cold-mb", type=int, default=600,
                     help="per-kernel timing rotates over tensor sets of at least this many MB in total")
@@ -75,7 +77,8 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
         per_donor = 4 if args.workload == "cfg1" else 1
         partial = os.path.join(ROOT, "gpurun_out", f"{args.workload}.pool.partial")
         pool = tune.tune_donors(donors, cfg + 100, args.level, log, per_donor,
-                                partial if os.path.isdir(os.path.dirname(partial)) else None, args.resume_pool or None)
+                                partial if os.path.isdir(os.path.dirname(partial)) else None, args.resume_pool or None,
+                                cold_mb=args.sweep_cold_mb)
         tune.save_pool(pool_path, pool, [donors[i // per_donor].name for i in range(len(pool))])
         pool_seconds = time.time() - t0
         mirror = os.path.join(ROOT, "gpurun_out", "tuned")
@@ -91,7 +94,9 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
         pool_seconds = None
     log(f"[sweep] transfer sweep: {len(dks)} kernels x {len(pool)} records")
     rows, table, evals, wall = api.tt_transfer_sweep(dks, pool, api.make_opts(**tune.FULL))
-    out = dict(workload=args.workload, pool_records=len(pool), pool_seconds=pool_seconds, transfer_pairs=evals,
+    out = dict(workload=args.workload, pool_records=len(pool), pool_seconds=pool_seconds,
+               sweep_timing=f"every launch of a pair on the next of enough tensor sets to hold {args.sweep_cold_mb} MB"
+               if args.sweep_cold_mb else "all launches of a pair on one tensor set (cache-warm)", transfer_pairs=evals,
                transfer_wall_seconds=wall, kernels=[])
     n_invalid = sum(r["n_invalid"] for r in rows)
     out["transfer_invalid_pairs"] = n_invalid
@@ -299,7 +304,7 @@ def main():
         keep = [i for i, k in enumerate(targets) if k.name in args.kernels.split(",")]
         assert keep and not args.sweep, "--kernels names no kernel of the workload (and cannot be combined with --sweep)"
         targets, seeds = [targets[i] for i in keep], [seeds[i] for i in keep]
-    dks = [harness.device_kernel(k, sd, max_split=8) for k, sd in zip(targets, seeds)]
+    dks = [harness.device_kernel(k, sd, max_split=8, cold_mb=args.sweep_cold_mb) for k, sd in zip(targets, seeds)]
     if args.sweep or not os.path.exists(tuned_path):
         tuned = run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_path)
         swept_here = True

@@ -319,7 +319,13 @@ int tt_dwconv(const void *x, const void *w, const void *bias, void *y, const tt_
               const tt_schedule *sched, void *stream);
 
 /* One target kernel of a sweep.  bufs: conv {x, w, bias, residual|NULL, y}; dense {x, w, bias, y, NULL};
- * batch matmul {a, b, c, NULL, NULL}; depthwise {x, w, bias, y, NULL}. */
+ * batch matmul {a, b, c, NULL, NULL}; depthwise {x, w, bias, y, NULL}.
+ * alt_bufs (host array of n_alt x 5 device pointers, NULL when n_alt = 0): further tensor sets of the same
+ * shapes.  The timing functions (tt_time_pair and every sweep) then walk round bufs and the alternatives
+ * launch by launch, so that a launch finds none of its operands in a cache once the sets together exceed the
+ * caches: the standalone time of a kernel whose inputs come from memory, as inside a network.  With n_alt = 0
+ * every launch of a pair reuses bufs (operands of repeated launches stay in the memory-side cache).
+ * tt_run_kernels uses bufs only. */
 typedef struct tt_kernel_desc {
     int32_t cls;
     int32_t use_count;  /* how often the network runs this kernel (Table 1's "Use Count") */
@@ -327,6 +333,8 @@ typedef struct tt_kernel_desc {
     void *bufs[5];      /* device                                                         */
     void *ws;           /* device workspace for split-K records, may be NULL              */
     size_t ws_bytes;
+    void *const *alt_bufs;
+    int32_t n_alt;
 } tt_kernel_desc;
 
 typedef struct tt_sweep_opts {

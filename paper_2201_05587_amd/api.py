@@ -79,7 +79,7 @@ class tt_plan(Structure):
 
 class tt_kernel_desc(Structure):
     _fields_ = [("cls", c_int32), ("use_count", c_int32), ("shape", c_void_p), ("bufs", c_void_p * 5),
-                ("ws", c_void_p), ("ws_bytes", c_size_t)]
+                ("ws", c_void_p), ("ws_bytes", c_size_t), ("alt_bufs", POINTER(c_void_p)), ("n_alt", c_int32)]
 
 
 class tt_sweep_opts(Structure):
@@ -374,11 +374,13 @@ def tt_debug_probe(which, src=None, dst=None, reps=10):
 class DeviceKernel:
     """A target kernel with its tensors resident on the GPU, ready for timing and sweeps."""
 
-    def __init__(self, cls, shape, tensors, use_count=1, name="", ws_bytes=0):
+    def __init__(self, cls, shape, tensors, use_count=1, name="", ws_bytes=0, alternates=()):
+        """alternates: further tensor dicts of the same shapes, which the timing functions rotate through."""
         torch = _torch()
         self.cls, self.name, self.use_count = cls, name, use_count
         self.cshape = to_c_shape(shape)
         self.tensors = tensors  # dict name -> device tensor (kept alive here)
+        self.alternates = list(alternates)
         self.ws = torch.empty(max(int(ws_bytes), 16), dtype=torch.uint8, device="cuda")
         if cls in CONV_CLASSES:
             order = ("x", "w", "bias", "res", "y")
@@ -394,6 +396,13 @@ class DeviceKernel:
             self.desc.bufs[i] = None if t is None else t.data_ptr()
         self.desc.ws = self.ws.data_ptr()
         self.desc.ws_bytes = self.ws.numel()
+        self.desc.n_alt = len(self.alternates)
+        self._alt = (c_void_p * max(5 * len(self.alternates), 1))()
+        for a, alt in enumerate(self.alternates):
+            for i, key in enumerate(order):
+                t = alt.get(key) if key else None
+                self._alt[5 * a + i] = None if t is None else t.data_ptr()
+        self.desc.alt_bufs = ctypes.cast(self._alt, POINTER(c_void_p)) if self.alternates else None
 
     def output(self):
         return self.tensors["c" if self.cls == TT_BATCH_MATMUL else "y"]

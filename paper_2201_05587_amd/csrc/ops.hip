@@ -268,20 +268,25 @@ extern "C" int tt_debug_tile_map(const tt_plan *plan, int32_t *out_dev, void *st
 
 namespace {
 
-int launch_kernel_desc(const tt_kernel_desc &k, const tt_schedule *sched, void *stream)
+// `turn` picks the tensor set: 0 = bufs, then the alternatives in order, round and round.
+int launch_kernel_desc(const tt_kernel_desc &k, const tt_schedule *sched, void *stream, int64_t turn = 0)
 {
+    void *const *b = k.bufs;
+    if (k.n_alt > 0) {
+        const int set = (int)(turn % (k.n_alt + 1));
+        if (set > 0) b = k.alt_bufs + (size_t)(set - 1) * 5;
+    }
     if (is_conv_class(k.cls))
-        return tt_conv2d_bias_relu(k.bufs[0], k.bufs[1], k.bufs[2], k.bufs[3], k.bufs[4],
-                                   static_cast<const tt_conv_shape *>(k.shape), k.cls, sched, k.ws, k.ws_bytes, stream);
+        return tt_conv2d_bias_relu(b[0], b[1], b[2], b[3], b[4], static_cast<const tt_conv_shape *>(k.shape), k.cls, sched,
+                                   k.ws, k.ws_bytes, stream);
     if (is_dense_class(k.cls))
-        return tt_dense_bias_relu(k.bufs[0], k.bufs[1], k.bufs[2], k.bufs[3],
-                                  static_cast<const tt_gemm_shape *>(k.shape), k.cls, sched, k.ws, k.ws_bytes, stream);
+        return tt_dense_bias_relu(b[0], b[1], b[2], b[3], static_cast<const tt_gemm_shape *>(k.shape), k.cls, sched, k.ws,
+                                  k.ws_bytes, stream);
     if (k.cls == TT_BATCH_MATMUL)
-        return tt_batch_matmul(k.bufs[0], k.bufs[1], k.bufs[2], static_cast<const tt_gemm_shape *>(k.shape), sched,
-                               k.ws, k.ws_bytes, stream);
+        return tt_batch_matmul(b[0], b[1], b[2], static_cast<const tt_gemm_shape *>(k.shape), sched, k.ws, k.ws_bytes,
+                               stream);
     if (k.cls == TT_DWCONV_BIAS_RELU6)
-        return tt_dwconv(k.bufs[0], k.bufs[1], k.bufs[2], k.bufs[3], static_cast<const tt_conv_shape *>(k.shape), sched,
-                         stream);
+        return tt_dwconv(b[0], b[1], b[2], b[3], static_cast<const tt_conv_shape *>(k.shape), sched, stream);
     return TT_ERR_BAD_ARG;
 }
 
@@ -333,17 +338,19 @@ int time_pair(const tt_kernel_desc &k, const tt_schedule *sched, const tt_sweep_
         if (rc != TT_OK) return rc;
         rec = &def;
     }
+    if (k.n_alt < 0 || (k.n_alt > 0 && !k.alt_bufs)) return TT_ERR_BAD_ARG;
     tt_plan plan;
     int rc = tt_schedule_apply(rec, k.cls, k.shape, o.flags, &plan);
     if (rc != TT_OK) return rc;
+    int64_t turn = 0; // launches so far: every launch moves on to the next tensor set
     for (int i = 0; i < std::max(1, o.warmup); ++i) {
-        rc = launch_kernel_desc(k, rec, s);
+        rc = launch_kernel_desc(k, rec, s, turn++);
         if (rc != TT_OK) return rc;
     }
     // Size a sample: time one launch, then batch enough launches to fill min_sample_us.
     float ms = 0.0f;
     if (hipEventRecord(t.e0, s) != hipSuccess) return TT_ERR_HIP;
-    rc = launch_kernel_desc(k, rec, s);
+    rc = launch_kernel_desc(k, rec, s, turn++);
     if (rc != TT_OK) return rc;
     if (hipEventRecord(t.e1, s) != hipSuccess || hipEventSynchronize(t.e1) != hipSuccess ||
         hipEventElapsedTime(&ms, t.e0, t.e1) != hipSuccess)
@@ -354,7 +361,7 @@ int time_pair(const tt_kernel_desc &k, const tt_schedule *sched, const tt_sweep_
     for (int smp = 0; smp < o.samples; ++smp) {
         if (hipEventRecord(t.e0, s) != hipSuccess) return TT_ERR_HIP;
         for (int l = 0; l < launches; ++l) {
-            rc = launch_kernel_desc(k, rec, s);
+            rc = launch_kernel_desc(k, rec, s, turn++);
             if (rc != TT_OK) return rc;
         }
         if (hipEventRecord(t.e1, s) != hipSuccess || hipEventSynchronize(t.e1) != hipSuccess ||

@@ -49,16 +49,25 @@ def max_workspace_bytes(kernel: wl.Kernel, max_split: int = 32) -> int:
     return 4 * max_split * b * m * n
 
 
-def device_kernel(kernel: wl.Kernel, seed: int, inputs: dict | None = None, max_split: int = 32) -> api.DeviceKernel:
-    """Upload a kernel's seeded inputs and allocate its output and split-K workspace."""
+def device_kernel(kernel: wl.Kernel, seed: int, inputs: dict | None = None, max_split: int = 32,
+                  cold_mb: float = 0.0) -> api.DeviceKernel:
+    """Upload a kernel's seeded inputs and allocate its output and split-K workspace.
+
+    cold_mb > 0 adds copies of every tensor (weights too: a network's layers do not share them) until all sets
+    together hold that many megabytes; the timing functions then rotate through them, so that every launch
+    reads its operands from memory (the caches hold 8 x 4 MB of L2 and 256 MB on the memory side)."""
     import torch
     host = inputs if inputs is not None else wl.make_inputs(kernel, seed)
     dt = kernel.shape.dtype
     tensors = {k: to_device(to_library_layout(kernel, k, v), dt) for k, v in host.items()}
     out_key = "c" if kernel.cls == wl.CLS_BATCH_MATMUL else "y"
     tensors[out_key] = torch.zeros(output_shape(kernel), dtype=api.torch_dtype(dt), device="cuda")
+    n_alt = 0
+    if cold_mb > 0:
+        n_alt = int(min(400, max(1, -(-cold_mb * 1e6 // kernel.algorithmic_bytes()))))
+    alternates = [{name: t.clone() for name, t in tensors.items()} for _ in range(n_alt)]
     return api.DeviceKernel(kernel.cls, kernel.shape, tensors, kernel.use_count, kernel.name,
-                            max_workspace_bytes(kernel, max_split))
+                            max_workspace_bytes(kernel, max_split), alternates)
 
 
 def bottleneck_chain(k_reduce: wl.Kernel, k_conv: wl.Kernel, k_expand: wl.Kernel, blocks: int, seed: int):

@@ -570,3 +570,29 @@ def test_machine_rate_probes_copy_exactly_and_report_plausible_rates(api):
         api.tt_debug_probe(api.TT_PROBE_COPY_LINEAR_GBPS, odd, odd, reps=1)
     with pytest.raises(api.TTError):
         api.tt_debug_probe(99, src, dst, reps=1)
+
+
+def test_timing_rotates_through_the_alternative_tensor_sets(api, P):
+    """With alternates every launch of a timed pair takes the next tensor set: all of them end up holding the
+    operator's output, and a streaming kernel timed over sets larger than the caches is not faster than on one."""
+    import torch
+    from paper_2201_05587_amd import harness
+    k = wl.Kernel(wl.CLS_CONV2D_BIAS_ADD_RELU, wl.ConvShape(32, 64, 56, 56, 256, 1, 1, 1, 1, 0, 0, wl.BF16), 1, "rotate")
+    warm = harness.device_kernel(k, 77)
+    cold = harness.device_kernel(k, 77, cold_mb=700.0)
+    assert len(cold.alternates) >= 6 and cold.desc.n_alt == len(cold.alternates)
+    for alt in cold.alternates:
+        alt["y"].fill_(float("nan"))
+    opts = api.make_opts(warmup=2, samples=5, min_sample_us=300, max_launches=32)
+    st_w, warm_us, _ = api.tt_time_pair(warm, None, opts)
+    st_c, cold_us, _ = api.tt_time_pair(cold, None, opts)
+    torch.cuda.synchronize()
+    assert st_w == api.TT_OK and st_c == api.TT_OK
+    for alt in cold.alternates:
+        assert torch.equal(alt["y"], warm.output())
+    assert torch.equal(cold.output(), warm.output())
+    assert cold_us > 0.9 * warm_us, (cold_us, warm_us)
+    # a descriptor that announces alternates without naming them is refused
+    cold.desc.alt_bufs = None
+    st, _, _ = api.tt_time_pair(cold, None, opts)
+    assert st == api.TT_ERR_BAD_ARG
