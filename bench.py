@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--no-live-sweep", action="store_true", help="do not repeat the sweeps after the timed region")
     ap.add_argument("--sweep-cold-mb", type=int, default=600,
                     help="megabytes of tensor sets the sweeps' launches rotate through (0: one set, cache-warm timing)")
+    ap.add_argument("--sweep-cold-min-mb", type=int, default=32,
+                    help="kernels whose tensors take less than this are timed on one tensor set in the sweeps")
     ap.add_argument("--kernels", default="", help="comma-separated kernel names: restrict the workload to them")
     ap.add_argument("--cold-mb", type=int, default=600,
                     help="per-kernel timing rotates over tensor sets of at least this many MB in total")
@@ -78,7 +80,7 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
         partial = os.path.join(ROOT, "gpurun_out", f"{args.workload}.pool.partial")
         pool = tune.tune_donors(donors, cfg + 100, args.level, log, per_donor,
                                 partial if os.path.isdir(os.path.dirname(partial)) else None, args.resume_pool or None,
-                                cold_mb=args.sweep_cold_mb)
+                                cold_mb=args.sweep_cold_mb, cold_min_mb=args.sweep_cold_min_mb)
         tune.save_pool(pool_path, pool, [donors[i // per_donor].name for i in range(len(pool))])
         pool_seconds = time.time() - t0
         mirror = os.path.join(ROOT, "gpurun_out", "tuned")
@@ -95,7 +97,8 @@ def run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_
     log(f"[sweep] transfer sweep: {len(dks)} kernels x {len(pool)} records")
     rows, table, evals, wall = api.tt_transfer_sweep(dks, pool, api.make_opts(**tune.FULL))
     out = dict(workload=args.workload, pool_records=len(pool), pool_seconds=pool_seconds,
-               sweep_timing=f"every launch of a pair on the next of enough tensor sets to hold {args.sweep_cold_mb} MB"
+               sweep_timing=f"kernels of at least {args.sweep_cold_min_mb} MB: every launch of a pair on the next of enough "
+                            f"tensor sets to hold {args.sweep_cold_mb} MB; smaller kernels on one tensor set"
                if args.sweep_cold_mb else "all launches of a pair on one tensor set (cache-warm)", transfer_pairs=evals,
                transfer_wall_seconds=wall, kernels=[])
     n_invalid = sum(r["n_invalid"] for r in rows)
@@ -304,7 +307,7 @@ def main():
         keep = [i for i, k in enumerate(targets) if k.name in args.kernels.split(",")]
         assert keep and not args.sweep, "--kernels names no kernel of the workload (and cannot be combined with --sweep)"
         targets, seeds = [targets[i] for i in keep], [seeds[i] for i in keep]
-    dks = [harness.device_kernel(k, sd, max_split=8, cold_mb=args.sweep_cold_mb) for k, sd in zip(targets, seeds)]
+    dks = [harness.device_kernel(k, sd, max_split=8, cold_mb=args.sweep_cold_mb, cold_min_mb=args.sweep_cold_min_mb) for k, sd in zip(targets, seeds)]
     if args.sweep or not os.path.exists(tuned_path):
         tuned = run_sweeps(args, api, tune, wl, targets, dks, donors, cfg, tuned_path, pool_path)
         swept_here = True
@@ -411,23 +414,36 @@ def main():
         g["flops"] += k.flops() * k.use_count
         g["bytes"] += k.algorithmic_bytes() * k.use_count
         g["launches"] += k.use_count
-    dom_name, in_pass = max(share.items(), key=lambda kv: kv[1]["us"])
-    dom = ledger[dom_name]
-    ridge_peak = PEAK["mfma_bf16"] if dom["dtype"] == wl.BF16 else PEAK["mfma_f32"]
-    ai = in_pass["flops"] / in_pass["bytes"]
-    if ai >= ridge_peak * 1e12 / (PEAK["hbm"] * 1e9):
-        roof = dict(bound="mfma", achieved=in_pass["flops"] / in_pass["us"] / 1e6, peak=ridge_peak, unit="TFLOP/s")
-    else:
-        roof = dict(bound="hbm", achieved=in_pass["bytes"] / in_pass["us"] / 1e3, peak=PEAK["hbm"], unit="GB/s")
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["share_of_pass"] = in_pass["us"] / sum(g["us"] for g in share.values())
-    roof["launches_per_pass"] = in_pass["launches"]
-    # HBM bytes per launch measured with rocprofv3 counters (paper_2201_05587_amd/traffic.py), reported
-    # only while the kernel sources are the ones the counters were taken on
-    roof["traffic"] = traffic.lookup(args.workload, dom_name)
-    roof.update(kernel=dom_name, avg_launch_us=in_pass["us"] / in_pass["launches"],
-                avg_launch_us_all_launches_of_this_process=dom["us"] / dom["launches"], launches=dom["launches"],
-                layers=sorted(dom["layers"]), arithmetic_intensity=ai, timing="cold: every launch on tensors that have left the caches")
+    pass_us = sum(g["us"] for g in share.values())
+
+    def roofline_of(name, in_pass):
+        led = ledger[name]
+        peak = PEAK["mfma_bf16"] if led["dtype"] == wl.BF16 else PEAK["mfma_f32"]
+        ai = in_pass["flops"] / in_pass["bytes"]
+        if ai >= peak * 1e12 / (PEAK["hbm"] * 1e9):
+            roof = dict(bound="mfma", achieved=in_pass["flops"] / in_pass["us"] / 1e6, peak=peak, unit="TFLOP/s")
+        else:
+            roof = dict(bound="hbm", achieved=in_pass["bytes"] / in_pass["us"] / 1e3, peak=PEAK["hbm"], unit="GB/s")
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        roof["share_of_pass"] = in_pass["us"] / pass_us
+        roof["launches_per_pass"] = in_pass["launches"]
+        # HBM bytes per launch measured with rocprofv3 counters (paper_2201_05587_amd/traffic.py), reported
+        # only while the kernel sources are the ones the counters were taken on
+        roof["traffic"] = traffic.lookup(args.workload, name)
+        roof.update(kernel=name, avg_launch_us=in_pass["us"] / in_pass["launches"],
+                    avg_launch_us_all_launches_of_this_process=led["us"] / led["launches"], launches=led["launches"],
+                    layers=sorted(led["layers"]), arithmetic_intensity=ai,
+                    timing="cold: every launch on tensors that have left the caches")
+        return roof
+
+    by_share = sorted(share.items(), key=lambda kv: -kv[1]["us"])
+    roof = roofline_of(*by_share[0])
+    ridge_peak = PEAK["mfma_bf16"] if ledger[by_share[0][0]]["dtype"] == wl.BF16 else PEAK["mfma_f32"]
+    # the symbol with the largest share among those bound by memory, and among those bound by the matrix cores
+    roof_by_bound = {}
+    for name, in_pass in by_share:
+        r = roofline_of(name, in_pass)
+        roof_by_bound.setdefault(r["bound"], r)
     groups = {n: dict(g, layers=sorted(g["layers"]), avg_us=g["us"] / g["launches"]) for n, g in ledger.items()}
     # the matrix-core-bound layers (arithmetic intensity above the ridge) against the MFMA peak
     mfma_bound = [dict(name=p["name"], tflops=p["tflops"], frac_of_mfma_peak=p["tflops"] / ridge_peak)
@@ -461,6 +477,7 @@ def main():
         "mfma_bound_layers": mfma_bound,
         "sweep": sweep,
         "roofline": roof,
+        "roofline_by_bound": roof_by_bound,
     }
     out["machine_rates"] = machine_rates(api)
     if not args.no_cpu_baseline:

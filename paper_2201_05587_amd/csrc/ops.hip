@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstdio>
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -342,15 +343,19 @@ int time_pair(const tt_kernel_desc &k, const tt_schedule *sched, const tt_sweep_
     tt_plan plan;
     int rc = tt_schedule_apply(rec, k.cls, k.shape, o.flags, &plan);
     if (rc != TT_OK) return rc;
-    int64_t turn = 0; // launches so far: every launch moves on to the next tensor set
+    // Launches so far, over all timed pairs of the process: every launch moves on to the next tensor set, and
+    // the next pair carries on where this one stops (a pair that started over at the first set would find it,
+    // and the few sets a short measurement touches, still in the memory-side cache from the pair before).
+    static std::atomic<int64_t> turns{0};
+    auto next_turn = [&]() { return turns.fetch_add(1, std::memory_order_relaxed); };
     for (int i = 0; i < std::max(1, o.warmup); ++i) {
-        rc = launch_kernel_desc(k, rec, s, turn++);
+        rc = launch_kernel_desc(k, rec, s, next_turn());
         if (rc != TT_OK) return rc;
     }
     // Size a sample: time one launch, then batch enough launches to fill min_sample_us.
     float ms = 0.0f;
     if (hipEventRecord(t.e0, s) != hipSuccess) return TT_ERR_HIP;
-    rc = launch_kernel_desc(k, rec, s, turn++);
+    rc = launch_kernel_desc(k, rec, s, next_turn());
     if (rc != TT_OK) return rc;
     if (hipEventRecord(t.e1, s) != hipSuccess || hipEventSynchronize(t.e1) != hipSuccess ||
         hipEventElapsedTime(&ms, t.e0, t.e1) != hipSuccess)
@@ -361,7 +366,7 @@ int time_pair(const tt_kernel_desc &k, const tt_schedule *sched, const tt_sweep_
     for (int smp = 0; smp < o.samples; ++smp) {
         if (hipEventRecord(t.e0, s) != hipSuccess) return TT_ERR_HIP;
         for (int l = 0; l < launches; ++l) {
-            rc = launch_kernel_desc(k, rec, s, turn++);
+            rc = launch_kernel_desc(k, rec, s, next_turn());
             if (rc != TT_OK) return rc;
         }
         if (hipEventRecord(t.e1, s) != hipSuccess || hipEventSynchronize(t.e1) != hipSuccess ||

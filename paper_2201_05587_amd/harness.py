@@ -50,12 +50,14 @@ def max_workspace_bytes(kernel: wl.Kernel, max_split: int = 32) -> int:
 
 
 def device_kernel(kernel: wl.Kernel, seed: int, inputs: dict | None = None, max_split: int = 32,
-                  cold_mb: float = 0.0) -> api.DeviceKernel:
+                  cold_mb: float = 0.0, cold_min_mb: float = 0.0) -> api.DeviceKernel:
     """Upload a kernel's seeded inputs and allocate its output and split-K workspace.
 
     cold_mb > 0 adds copies of every tensor (weights too: a network's layers do not share them) until all sets
     together hold that many megabytes; the timing functions then rotate through them, so that every launch
-    reads its operands from memory (the caches hold 8 x 4 MB of L2 and 256 MB on the memory side)."""
+    reads its operands from memory (the caches hold 8 x 4 MB of L2 and 256 MB on the memory side).  Kernels
+    whose tensors take less than cold_min_mb get no copies: what fits the L2s a kernel finds there inside a
+    network, just written by its producer, and timing it on one set ranks records with far less noise."""
     import torch
     host = inputs if inputs is not None else wl.make_inputs(kernel, seed)
     dt = kernel.shape.dtype
@@ -63,7 +65,7 @@ def device_kernel(kernel: wl.Kernel, seed: int, inputs: dict | None = None, max_
     out_key = "c" if kernel.cls == wl.CLS_BATCH_MATMUL else "y"
     tensors[out_key] = torch.zeros(output_shape(kernel), dtype=api.torch_dtype(dt), device="cuda")
     n_alt = 0
-    if cold_mb > 0:
+    if cold_mb > 0 and kernel.algorithmic_bytes() >= cold_min_mb * 1e6:
         n_alt = int(min(400, max(1, -(-cold_mb * 1e6 // kernel.algorithmic_bytes()))))
     alternates = [{name: t.clone() for name, t in tensors.items()} for _ in range(n_alt)]
     return api.DeviceKernel(kernel.cls, kernel.shape, tensors, kernel.use_count, kernel.name,

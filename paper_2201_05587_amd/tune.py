@@ -60,13 +60,14 @@ def fastest_distinct_tiles(dk: api.DeviceKernel, level: int, count: int, tiles=(
 
 def tune_donors(kernels: Sequence[wl.Kernel], seed_cfg: int, level: int = 1, log=None,
                 records_per_donor: int = 1, checkpoint: Optional[str] = None,
-                resume: Optional[str] = None, cold_mb: float = 0.0) -> List[api.tt_schedule]:
+                resume: Optional[str] = None, cold_mb: float = 0.0, cold_min_mb: float = 0.0) -> List[api.tt_schedule]:
     """Native-tune every donor kernel; each contributes its optimum as one pool record (or, with
     records_per_donor > 1, its fastest records of pairwise distinct workgroup tiles).
 
     With `checkpoint` the pool so far is written to that file after every donor; `resume` names such a
     file of an earlier run, whose donors are not tuned again (a long tuning job may be cut short).
-    cold_mb: megabytes of tensor sets every pair's launches rotate through (0: one set, cache-warm timing).
+    cold_mb, cold_min_mb: megabytes of tensor sets every pair's launches rotate through (0: one set, cache-warm
+    timing), for donors whose tensors take at least cold_min_mb.
     """
     import os
     import torch
@@ -82,7 +83,7 @@ def tune_donors(kernels: Sequence[wl.Kernel], seed_cfg: int, level: int = 1, log
             continue
         if checkpoint and records_per_donor == 1 and pool:
             save_pool(checkpoint, pool, [kk.name for kk in kernels[:len(pool)]])
-        dk = harness.device_kernel(k, wl.seed_for(seed_cfg, i), max_split=8, cold_mb=cold_mb)
+        dk = harness.device_kernel(k, wl.seed_for(seed_cfg, i), max_split=8, cold_mb=cold_mb, cold_min_mb=cold_min_mb)
         t0 = time.time()
         if records_per_donor > 1:
             for rec, us in fastest_distinct_tiles(dk, level, records_per_donor):
