@@ -150,7 +150,7 @@ def counters_table(directories) -> str:
     for d in directories:
         for r in _rows(d):
             s = _symbol(r["Kernel_Name"])
-            if "tt::" not in s:
+            if "tt::" not in s or "probe_" in s:
                 continue
             c = r["Counter_Name"]
             if c not in names:
