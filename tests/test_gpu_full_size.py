@@ -132,6 +132,12 @@ def test_cfg5_resnet50_b32_bf16_whole(index):
     run_whole("cfg5", index)
 
 
+@pytest.mark.parametrize("index", cases_of("cfg1"))
+def test_cfg1_conv_fp32_whole(index):
+    """The single convolution of the smallest configuration under the records its four-record pool gave it."""
+    run_whole("cfg1", index)
+
+
 @pytest.mark.parametrize("index", cases_of("cfg2"))
 def test_cfg2_resnet18_fp32_whole(index):
     run_whole("cfg2", index)
