@@ -178,20 +178,34 @@ template <int DT> __device__ __forceinline__ u32x4 keep_first(u32x4 v, int keep)
     return v;
 }
 
-// Zero the elements of a 16-byte item at positions outside [lo, hi).
-template <int DT> __device__ __forceinline__ u32x4 keep_range(u32x4 v, int lo, int hi)
-{
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-        if constexpr (DT == TT_F32) {
-            v[h] = ((h >= lo) & (h < hi)) ? v[h] : 0u;
-        } else {
-            const uint32_t low = ((2 * h >= lo) & (2 * h < hi)) ? 0xffffu : 0u;
-            const uint32_t high = ((2 * h + 1 >= lo) & (2 * h + 1 < hi)) ? 0xffff0000u : 0u;
-            v[h] &= low | high;
-        }
+// Masks that zero the elements of a 16-byte item at positions outside [lo, hi), 0 <= lo <= hi <= elements
+// per item, as a table in device memory indexed by lo * (CH + 1) + hi.  The element-wise gather is bound by
+// vector instructions: it asks for an item's mask when it requests the item (one more load in flight, from
+// a table of a few cache lines) and applies it with four ANDs when the item goes to LDS, where building the
+// mask from range compares took about 25 instructions per item.
+template <int DT> struct RangeMasks {
+    static constexpr int CH = DT == TT_BF16 ? 8 : 4;
+    uint32_t w[(CH + 1) * (CH + 1)][4];
+    constexpr RangeMasks() : w{}
+    {
+        for (int lo = 0; lo <= CH; ++lo)
+            for (int hi = lo; hi <= CH; ++hi)
+                for (int e = lo; e < hi; ++e) {
+                    if (DT == TT_BF16)
+                        w[lo * (CH + 1) + hi][e / 2] |= 0xffffu << (16 * (e % 2));
+                    else
+                        w[lo * (CH + 1) + hi][e] = 0xffffffffu;
+                }
     }
-    return v;
+};
+static __device__ const RangeMasks<TT_BF16> kRangeMasksBf16{};
+static __device__ const RangeMasks<TT_F32> kRangeMasksF32{};
+template <int DT> __device__ __forceinline__ u32x4 range_mask(int lo, int hi)
+{
+    if constexpr (DT == TT_BF16)
+        return *reinterpret_cast<const u32x4 *>(kRangeMasksBf16.w[lo * 9 + hi]);
+    else
+        return *reinterpret_cast<const u32x4 *>(kRangeMasksF32.w[lo * 5 + hi]);
 }
 
 // Rows of a K-contiguous matrix [rows_total][K], K >= CH: each thread fetches 16-byte chunks along
@@ -287,8 +301,9 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
         int32_t jlo[NL], jhi[NL];
         int32_t r, j, dr, dj, runp, row_stride, numel;
         u32x4 raw[NL];
-        int32_t span[NL]; // without VEC: first real element of the item in flight | (one past the last) << 8
-                          // | bf16: (the item starts in the upper half of its first 32-bit word) << 16
+        int32_t span[NL]; // without VEC, bf16: 2 if the item in flight starts in the upper half of its first
+                          // 32-bit word (the bytes to shift it down by), else 0
+        u32x4 mask[NL];   // without VEC: ones over the real elements of the item in flight
         uint32_t tail[NL]; // bf16 without VEC: the 32-bit word after raw (the item's last element if it starts odd)
     };
 
@@ -350,7 +365,8 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
                 const int lo = min(max(st.jlo[i] - st.j, 0), CH), hi = min(max(st.jhi[i] - st.j, 0), CH);
                 const bool any = row_ok & (hi > lo);
                 const int start = st.origin[i] + kterm;
-                st.span[i] = any ? (lo | (hi << 8)) : 0;
+                st.span[i] = 0;
+                st.mask[i] = range_mask<DT>(any ? lo : 0, any ? hi : 0);
                 if constexpr (DT == TT_BF16) st.tail[i] = 0u;
                 if (!any || (start >= 0 && start + CH + 2 <= st.numel)) {
                     if constexpr (DT == TT_BF16) {
@@ -360,7 +376,7 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
                         const uint32_t at4 = at & ~3u;
                         st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, any ? at4 : kOutOfRange, 0, 0);
                         st.tail[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, any ? at4 + 16u : kOutOfRange, 0, 0);
-                        st.span[i] |= (int32_t)(at & 2u) << 15;
+                        st.span[i] = (int32_t)(at & 2u);
                     } else {
                         st.raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, any ? at : kOutOfRange, 0, 0);
                     }
@@ -400,12 +416,11 @@ template <int DT, int ROWS, int TK, int THREADS, bool VEC, bool WEIGHTS> struct 
             u32x4 v = st.raw[i];
             if constexpr (!VEC) {
                 if constexpr (DT == TT_BF16) {
-                    if (st.span[i] & (1 << 16)) {
-                        v = u32x4{__builtin_amdgcn_alignbyte(v[1], v[0], 2), __builtin_amdgcn_alignbyte(v[2], v[1], 2),
-                                  __builtin_amdgcn_alignbyte(v[3], v[2], 2), __builtin_amdgcn_alignbyte(st.tail[i], v[3], 2)};
-                    }
+                    const uint32_t sh = (uint32_t)st.span[i]; // 0 leaves the words as they are
+                    v = u32x4{__builtin_amdgcn_alignbyte(v[1], v[0], sh), __builtin_amdgcn_alignbyte(v[2], v[1], sh),
+                              __builtin_amdgcn_alignbyte(v[3], v[2], sh), __builtin_amdgcn_alignbyte(st.tail[i], v[3], sh)};
                 }
-                v = keep_range<DT>(v, st.span[i] & 0xff, (st.span[i] >> 8) & 0xff);
+                v &= st.mask[i];
             }
             *reinterpret_cast<u32x4 *>(lds + row * ROWB + chunk * 16) = v;
         }
